@@ -1,0 +1,121 @@
+/*
+ * axonn_linear -- the per-GPU matrix multiplies of a tensor-parallel FC layer
+ * on AMD MI355X (CDNA4, gfx950), as a plain C ABI.
+ *
+ * An FC layer performs one half-precision matrix multiply in the forward pass
+ * and two in the backward pass (paper Sec. IV-A, paragraph introducing the
+ * three multiplies; Algorithm 1 lines 3, 11 and 13):
+ *
+ *     forward           O      = I     x W        axonn_linear_fwd
+ *     backward, data    dL/dI  = dL/dO x W^T      axonn_linear_bwd_data
+ *     backward, weight  dL/dW  = I^T   x dL/dO    axonn_linear_bwd_weight
+ *
+ * Each call is  C[M,N] = sum over k < K of a(i,k) * b(k,j)  with bf16 operands,
+ * fp32 accumulation over the whole K range and one round-to-nearest-even
+ * conversion to bf16 at the store.  M, N, K are the dimensions of THIS product
+ * (output M x N, reduction length K), not of the layer.
+ *
+ * `layout` is the mode of Sec. IV-C (NN, NT, TN), in row-major terms, first
+ * letter = first operand:
+ *
+ *     AXONN_NN   first is [M,K], second is [K,N]     C = A   * B
+ *     AXONN_NT   first is [M,K], second is [N,K]     C = A   * B^T
+ *     AXONN_TN   first is [K,M], second is [K,N]     C = A^T * B
+ *
+ * (A column-major BLAS names the same three storage patterns NN, TN and NT.)
+ * With the buffers the method keeps from the forward pass -- I as [tokens,in],
+ * W as [in,out], dL/dO as [tokens,out] -- the natural calls are
+ *     fwd       (tokens, out, in,     AXONN_NN, I,     W,     O )
+ *     bwd_data  (tokens, in,  out,    AXONN_NT, dL/dO, W,     dL/dI)
+ *     bwd_weight(in,     out, tokens, AXONN_TN, I,     dL/dO, dL/dW)
+ * and the other six (function, layout) pairs expect the caller to hold a
+ * transposed copy of one operand.
+ *
+ * Common rules for the three entry points
+ *   pointers   DEVICE pointers to bf16 (16-bit) elements, row-major, tightly
+ *              packed, 16-byte aligned.  The caller owns all three buffers; the
+ *              library allocates nothing, keeps no reference after return and
+ *              never reads the output.  The output must not overlap an input.
+ *   stream     a hipStream_t passed as void*; NULL is the default stream.  The
+ *              call enqueues work and returns; it never synchronises.
+ *   fp32_accumulate
+ *              1: fp32 accumulators over all of K, one rounding at the store.
+ *              0: the caller does not require fp32; the same kernels run (the
+ *              bf16 matrix instructions of CDNA4 accumulate in fp32 anyway), so
+ *              0 is never less accurate than 1.  Other values: INVALID_ARG.
+ *   sizes      M, N, K >= 0, each below 2^31, and each operand below 2^40 elements.
+ *              M == 0 or N == 0: nothing to do, AXONN_OK.  K == 0: the output is
+ *              set to +0.  Any M, N, K is computed correctly; the fast tiled
+ *              kernels need M and N to be multiples of 128 and K of 64, other
+ *              shapes take a slower guarded kernel.
+ *   errors     the return value is AXONN_OK (0) or a negative code below; on an
+ *              error nothing has been launched.  No exceptions, no aborts.
+ *   threads    re-entrant; the only process-wide state is the kernel override
+ *              (axonn_linear_force_variant) used by tests and the benchmark.
+ *   determinism the same inputs give the same bits on every call: no atomics,
+ *              fixed summation order per kernel variant.
+ */
+#ifndef AXONN_LINEAR_H
+#define AXONN_LINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { AXONN_NN = 0, AXONN_NT = 1, AXONN_TN = 2 } axonn_layout_t;
+
+enum {
+    AXONN_OK = 0,
+    AXONN_ERR_INVALID_ARG = -1, /* null / misaligned pointer, negative or oversized dim, bad enum or flag */
+    AXONN_ERR_UNSUPPORTED = -2, /* a forced kernel variant cannot run this shape */
+    AXONN_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
+};
+
+/* Forward, Algorithm 1 line 3:  Y[M,N] = X * W.  X and W stored as `layout` says. */
+int axonn_linear_fwd(int64_t M, int64_t N, int64_t K, int layout,
+                     const void *X, const void *W, void *Y,
+                     int fp32_accumulate, void *stream);
+
+/* Backward w.r.t. the input, Algorithm 1 line 11:  dX[M,N] = dY * W^T.
+ * M = tokens, N = in features, K = out features; dY is the first operand, W the second
+ * (AXONN_NT takes W exactly as the forward pass stored it, [in,out] = [N,K]). */
+int axonn_linear_bwd_data(int64_t M, int64_t N, int64_t K, int layout,
+                          const void *dY, const void *W, void *dX,
+                          int fp32_accumulate, void *stream);
+
+/* Backward w.r.t. the weight, Algorithm 1 line 13:  dW[M,N] = X^T * dY.
+ * M = in features, N = out features, K = tokens; X is the first operand, dY the second
+ * (AXONN_TN takes both exactly as stored, [tokens,in] = [K,M] and [tokens,out] = [K,N]). */
+int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout,
+                            const void *X, const void *dY, void *dW,
+                            int fp32_accumulate, void *stream);
+
+/* ---- support ---------------------------------------------------------------------------- */
+
+/* Human-readable text for a status code; never NULL; static storage. */
+const char *axonn_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int axonn_linear_version(void);
+
+/* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any
+ * shape; the others are MFMA tile kernels.  Host-only queries: no GPU is touched. */
+int axonn_linear_num_variants(void);
+/* Name such as "mfma_256x256_w2x2"; NULL if `variant` is out of range. */
+const char *axonn_linear_variant_name(int variant);
+/* 1 if `variant` can run (M,N,K,layout), else 0. */
+int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout);
+/* The variant the library would pick for this problem (pure host logic, ignores any override);
+ * negative error code on bad arguments. */
+int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout);
+/* Override the choice for all later calls in this process; -1 restores automatic selection.
+ * Returns AXONN_OK or AXONN_ERR_INVALID_ARG.  For tests, tuning and the benchmark. */
+int axonn_linear_force_variant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AXONN_LINEAR_H */

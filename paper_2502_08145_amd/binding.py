@@ -1,0 +1,146 @@
+"""Python face of libaxonn_linear.so: argument marshalling only.
+
+Every function here has the name and the argument order of the C entry point it calls
+(include/axonn_linear.h).  Tensors are torch bf16 CUDA tensors used purely as device memory;
+no arithmetic happens in Python or in torch.  If the library has not been built the import
+of a symbol fails loudly -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # noqa: F401  (imported before the library so both share one HIP runtime)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libaxonn_linear.so")
+
+AXONN_NN, AXONN_NT, AXONN_TN = 0, 1, 2
+LAYOUTS = {"NN": AXONN_NN, "NT": AXONN_NT, "TN": AXONN_TN}
+AXONN_OK, AXONN_ERR_INVALID_ARG, AXONN_ERR_UNSUPPORTED, AXONN_ERR_LAUNCH = 0, -1, -2, -3
+
+EXPORTS = (
+    "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
+    "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
+    "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
+    "axonn_linear_force_variant",
+)
+
+_lib = None
+
+
+class AxonnError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2502_08145_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        for name in ("axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight"):
+            fn = getattr(L, name)
+            fn.argtypes = [i64, i64, i64, ci, vp, vp, vp, ci, vp]
+            fn.restype = ci
+        L.axonn_status_string.argtypes = [ci]
+        L.axonn_status_string.restype = ctypes.c_char_p
+        L.axonn_linear_version.argtypes = []
+        L.axonn_linear_version.restype = ci
+        L.axonn_linear_num_variants.argtypes = []
+        L.axonn_linear_num_variants.restype = ci
+        L.axonn_linear_variant_name.argtypes = [ci]
+        L.axonn_linear_variant_name.restype = ctypes.c_char_p
+        L.axonn_linear_variant_supports.argtypes = [ci, i64, i64, i64, ci]
+        L.axonn_linear_variant_supports.restype = ci
+        L.axonn_linear_select_variant.argtypes = [i64, i64, i64, ci]
+        L.axonn_linear_select_variant.restype = ci
+        L.axonn_linear_force_variant.argtypes = [ci]
+        L.axonn_linear_force_variant.restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().axonn_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().axonn_linear_version()
+
+
+def num_variants() -> int:
+    return lib().axonn_linear_num_variants()
+
+
+def variant_name(v: int):
+    s = lib().axonn_linear_variant_name(int(v))
+    return s.decode() if s is not None else None
+
+
+def variant_supports(v: int, M: int, N: int, K: int, layout) -> bool:
+    return bool(lib().axonn_linear_variant_supports(int(v), M, N, K, _layout(layout)))
+
+
+def select_variant(M: int, N: int, K: int, layout) -> int:
+    return lib().axonn_linear_select_variant(M, N, K, _layout(layout))
+
+
+def force_variant(v: int) -> None:
+    rc = lib().axonn_linear_force_variant(int(v))
+    if rc != AXONN_OK:
+        raise AxonnError(rc, "axonn_linear_force_variant")
+
+
+def _layout(layout) -> int:
+    return LAYOUTS[layout] if isinstance(layout, str) else int(layout)
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError("expected a contiguous bf16 CUDA tensor")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _call(name, M, N, K, layout, a, b, c, fp32_accumulate, stream, check):
+    rc = getattr(lib(), name)(int(M), int(N), int(K), _layout(layout), _ptr(a), _ptr(b), _ptr(c),
+                              int(fp32_accumulate), _stream(stream))
+    if check and rc != AXONN_OK:
+        raise AxonnError(rc, name)
+    return rc
+
+
+def axonn_linear_fwd(M, N, K, layout, X, W, Y, fp32_accumulate=1, stream=None, check=True):
+    """Y[M,N] = X * W (Algorithm 1 line 3); X, W stored as `layout` says; Y is written."""
+    return _call("axonn_linear_fwd", M, N, K, layout, X, W, Y, fp32_accumulate, stream, check)
+
+
+def axonn_linear_bwd_data(M, N, K, layout, dY, W, dX, fp32_accumulate=1, stream=None, check=True):
+    """dX[M,N] = dY * W^T (Algorithm 1 line 11)."""
+    return _call("axonn_linear_bwd_data", M, N, K, layout, dY, W, dX, fp32_accumulate, stream, check)
+
+
+def axonn_linear_bwd_weight(M, N, K, layout, X, dY, dW, fp32_accumulate=1, stream=None, check=True):
+    """dW[M,N] = X^T * dY (Algorithm 1 line 13)."""
+    return _call("axonn_linear_bwd_weight", M, N, K, layout, X, dY, dW, fp32_accumulate, stream, check)
+
+
+OPS = {"fwd": axonn_linear_fwd, "bwd_data": axonn_linear_bwd_data, "bwd_weight": axonn_linear_bwd_weight}

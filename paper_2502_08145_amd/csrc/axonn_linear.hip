@@ -1,0 +1,218 @@
+// C ABI of the FC-layer GEMM library (see include/axonn_linear.h for the contract).
+// Host side: argument checks, kernel-variant selection, launch.  No device memory is
+// allocated here and nothing synchronises.
+#include "../../include/axonn_linear.h"
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <mutex>
+
+#include "gemm_mfma.hpp"
+
+namespace axonn {
+
+// ------------------------------------------------------------------------------------------
+// Variant 0: guarded kernel, one thread per output element, any M, N, K >= 0.
+// fp32 accumulation in ascending k, one RNE rounding at the store.
+// ------------------------------------------------------------------------------------------
+template <int LAYOUT>
+__global__ __launch_bounds__(256) void gemm_naive_kernel(const uint16_t* __restrict__ A,
+                                                         const uint16_t* __restrict__ B,
+                                                         uint16_t* __restrict__ C, int64_t M,
+                                                         int64_t N, int64_t K) {
+    const int64_t j = (int64_t)blockIdx.x * 16 + (threadIdx.x & 15);
+    const int64_t i = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (i >= M || j >= N) return;
+    float acc = 0.f;
+    for (int64_t k = 0; k < K; ++k) {
+        const uint16_t a = (LAYOUT == AXONN_TN) ? A[k * M + i] : A[i * K + k];
+        const uint16_t b = (LAYOUT == AXONN_NT) ? B[j * K + k] : B[k * N + j];
+        acc += __builtin_bit_cast(float, (uint32_t)a << 16) * __builtin_bit_cast(float, (uint32_t)b << 16);
+    }
+    C[i * N + j] = (uint16_t)f32_to_bf16_rne(acc);
+}
+
+// ------------------------------------------------------------------------------------------
+// Variant table
+// ------------------------------------------------------------------------------------------
+typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int);
+
+struct Variant {
+    const char* name;
+    int bm, bn, threads, lds_bytes;  // bm == 0: the naive kernel
+    tile_kernel_t fn[3];             // per layout
+};
+
+#define AXONN_TILE_VARIANT(BM, BN, WM, WN)                                                   \
+    {                                                                                        \
+        "mfma_" #BM "x" #BN "_w" #WM "x" #WN, BM, BN, WM* WN * 64,                           \
+            TileCfg<BM, BN, WM, WN>::LDS_BYTES, {                                            \
+            gemm_tile_kernel<BM, BN, WM, WN, true, false>,                                   \
+                gemm_tile_kernel<BM, BN, WM, WN, true, true>,                                \
+                gemm_tile_kernel<BM, BN, WM, WN, false, false>                               \
+        }                                                                                    \
+    }
+
+static const Variant g_variants[] = {
+    {"naive", 0, 0, 256, 0, {nullptr, nullptr, nullptr}},
+    AXONN_TILE_VARIANT(256, 256, 2, 2),
+    AXONN_TILE_VARIANT(256, 256, 2, 4),
+    AXONN_TILE_VARIANT(256, 128, 2, 2),
+    AXONN_TILE_VARIANT(128, 256, 2, 2),
+    AXONN_TILE_VARIANT(128, 128, 2, 2),
+};
+constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
+
+static std::atomic<int> g_forced{-1};
+static std::once_flag g_attr_once;
+
+static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout) {
+    if (v < 0 || v >= kNumVariants || layout < 0 || layout > 2) return false;
+    const Variant& var = g_variants[v];
+    if (var.bm == 0) return true;
+    if (M <= 0 || N <= 0 || K <= 0) return false;
+    return M % var.bm == 0 && N % var.bn == 0 && K % BK == 0;
+}
+
+// MI355X has 256 compute units; a grid of fewer tiles than that leaves units idle, and the last
+// partial wave of tiles costs a whole tile time.  Pick the tile shape with the best modelled
+// time: (waves of tiles over 256 CUs) x (tile area) / (per-shape efficiency).
+static int select_variant(int64_t M, int64_t N, int64_t K, int layout) {
+    static const struct { int v; double eff; } cand[] = {{1, 1.00}, {3, 0.85}, {4, 0.85}, {5, 0.70}};
+    int best = 0;
+    double best_t = 0;
+    for (const auto& c : cand) {
+        if (!variant_supports(c.v, M, N, K, layout)) continue;
+        const Variant& var = g_variants[c.v];
+        const int64_t tiles = (M / var.bm) * (N / var.bn);
+        // workgroups resident per CU is limited by LDS (160 KB per CU)
+        const int per_cu = var.lds_bytes > 80 * 1024 ? 1 : 2;
+        const int64_t slots = 256 * per_cu;
+        const int64_t waves = (tiles + slots - 1) / slots;
+        const double t = (double)waves * var.bm * var.bn * per_cu / c.eff;
+        if (best == 0 || t < best_t) {
+            best = c.v;
+            best_t = t;
+        }
+    }
+    return best;
+}
+
+static int check_args(int64_t M, int64_t N, int64_t K, int layout, const void* a, const void* b,
+                      void* c, int fp32_accumulate) {
+    constexpr int64_t kMaxDim = (int64_t)1 << 31, kMaxElems = (int64_t)1 << 40;
+    if (M < 0 || N < 0 || K < 0 || M >= kMaxDim || N >= kMaxDim || K >= kMaxDim) return AXONN_ERR_INVALID_ARG;
+    if (layout < 0 || layout > 2) return AXONN_ERR_INVALID_ARG;
+    if (fp32_accumulate != 0 && fp32_accumulate != 1) return AXONN_ERR_INVALID_ARG;
+    if (M * K >= kMaxElems || K * N >= kMaxElems || M * N >= kMaxElems) return AXONN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return AXONN_OK;
+    if (!c || (reinterpret_cast<uintptr_t>(c) & 15)) return AXONN_ERR_INVALID_ARG;
+    if (K > 0) {
+        if (!a || !b) return AXONN_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(a) & 15) || (reinterpret_cast<uintptr_t>(b) & 15))
+            return AXONN_ERR_INVALID_ARG;
+    }
+    return AXONN_OK;
+}
+
+static void raise_lds_limits() {
+    for (int v = 1; v < kNumVariants; ++v)
+        for (int l = 0; l < 3; ++l)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(g_variants[v].fn[l]),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, g_variants[v].lds_bytes);
+    (void)hipGetLastError();
+}
+
+static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, const void* b, void* c,
+                  int fp32_accumulate, void* stream) {
+    const int rc = check_args(M, N, K, layout, a, b, c, fp32_accumulate);
+    if (rc != AXONN_OK) return rc;
+    if (M == 0 || N == 0) return AXONN_OK;
+
+    int v = g_forced.load(std::memory_order_relaxed);
+    if (v >= 0) {
+        if (!variant_supports(v, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
+    } else {
+        v = select_variant(M, N, K, layout);
+    }
+    const Variant& var = g_variants[v];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint16_t* A = static_cast<const uint16_t*>(a);
+    const uint16_t* B = static_cast<const uint16_t*>(b);
+    uint16_t* C = static_cast<uint16_t*>(c);
+
+    (void)hipGetLastError();
+    if (var.bm == 0) {
+        const dim3 grid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16));
+        if (grid.y > 65535u * 16u) return AXONN_ERR_UNSUPPORTED;
+        switch (layout) {
+            case AXONN_NN: hipLaunchKernelGGL(gemm_naive_kernel<AXONN_NN>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
+            case AXONN_NT: hipLaunchKernelGGL(gemm_naive_kernel<AXONN_NT>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
+            default:       hipLaunchKernelGGL(gemm_naive_kernel<AXONN_TN>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
+        }
+    } else {
+        std::call_once(g_attr_once, raise_lds_limits);
+        const int tiles_m = (int)(M / var.bm), tiles_n = (int)(N / var.bn);
+        const int64_t tiles = (int64_t)tiles_m * tiles_n;
+        if (tiles >= ((int64_t)1 << 31)) return AXONN_ERR_UNSUPPORTED;
+        const int group_m = tiles_m < 8 ? tiles_m : 8;
+        hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)tiles), dim3(var.threads), var.lds_bytes, s, A, B, C,
+                           (int)M, (int)N, (int)K, tiles_m, tiles_n, group_m);
+    }
+    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
+}
+
+}  // namespace axonn
+
+extern "C" {
+
+int axonn_linear_fwd(int64_t M, int64_t N, int64_t K, int layout, const void* X, const void* W, void* Y,
+                     int fp32_accumulate, void* stream) {
+    return axonn::launch(M, N, K, layout, X, W, Y, fp32_accumulate, stream);
+}
+
+int axonn_linear_bwd_data(int64_t M, int64_t N, int64_t K, int layout, const void* dY, const void* W, void* dX,
+                          int fp32_accumulate, void* stream) {
+    return axonn::launch(M, N, K, layout, dY, W, dX, fp32_accumulate, stream);
+}
+
+int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout, const void* X, const void* dY, void* dW,
+                            int fp32_accumulate, void* stream) {
+    return axonn::launch(M, N, K, layout, X, dY, dW, fp32_accumulate, stream);
+}
+
+const char* axonn_status_string(int status) {
+    switch (status) {
+        case AXONN_OK: return "ok";
+        case AXONN_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad dimension, layout or flag)";
+        case AXONN_ERR_UNSUPPORTED: return "the forced kernel variant cannot run this shape";
+        case AXONN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int axonn_linear_version(void) { return 100; }
+
+int axonn_linear_num_variants(void) { return axonn::kNumVariants; }
+
+const char* axonn_linear_variant_name(int variant) {
+    return (variant >= 0 && variant < axonn::kNumVariants) ? axonn::g_variants[variant].name : nullptr;
+}
+
+int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout) {
+    return axonn::variant_supports(variant, M, N, K, layout) ? 1 : 0;
+}
+
+int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
+    if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 2) return AXONN_ERR_INVALID_ARG;
+    return axonn::select_variant(M, N, K, layout);
+}
+
+int axonn_linear_force_variant(int variant) {
+    if (variant < -1 || variant >= axonn::kNumVariants) return AXONN_ERR_INVALID_ARG;
+    axonn::g_forced.store(variant, std::memory_order_relaxed);
+    return AXONN_OK;
+}
+
+}  // extern "C"

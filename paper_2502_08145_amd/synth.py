@@ -13,6 +13,9 @@ so that no input is subnormal in bf16.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 _MASK64 = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -46,20 +49,42 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def normal_bf16(seed: int, shape, sigma: float = 1.0, chunk: int = 1 << 22) -> np.ndarray:
-    """N(0, sigma^2) samples as bf16 bits, shape `shape`, row-major element numbering."""
+def _normal_chunk(seed: int, start: int, cnt: int, sigma: float) -> np.ndarray:
+    h = _hash_stream(seed, cnt, start)
+    u1 = ((h >> np.uint64(32)).astype(np.float64) + 1.0) / 4294967296.0   # (0, 1]
+    u2 = (h & np.uint64(0xFFFFFFFF)).astype(np.float64) / 4294967296.0    # [0, 1)
+    z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    v = (z * sigma).astype(np.float32)
+    v[np.abs(v) < np.float32(2.0 ** -120)] = 0.0
+    return f32_to_bf16_bits(v)
+
+
+def normal_bf16(seed: int, shape, sigma: float = 1.0, chunk: int = 1 << 20, workers: int | None = None) -> np.ndarray:
+    """N(0, sigma^2) samples as bf16 bits, shape `shape`, row-major element numbering.
+
+    The result does not depend on `chunk` or `workers` (element n is a function of (seed, n)).
+    """
     shape = tuple(int(s) for s in shape)
     total = int(np.prod(shape)) if shape else 1
     out = np.empty(total, dtype=np.uint16)
-    for start in range(0, total, chunk):
+    starts = list(range(0, total, chunk))
+    if workers is None:
+        try:
+            workers = len(os.sched_getaffinity(0))
+        except AttributeError:  # pragma: no cover
+            workers = os.cpu_count() or 1
+        workers = max(1, min(16, workers))
+
+    def work(start):
         cnt = min(chunk, total - start)
-        h = _hash_stream(seed, cnt, start)
-        u1 = ((h >> np.uint64(32)).astype(np.float64) + 1.0) / 4294967296.0   # (0, 1]
-        u2 = (h & np.uint64(0xFFFFFFFF)).astype(np.float64) / 4294967296.0    # [0, 1)
-        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-        v = (z * sigma).astype(np.float32)
-        v[np.abs(v) < np.float32(2.0 ** -120)] = 0.0
-        out[start:start + cnt] = f32_to_bf16_bits(v)
+        out[start:start + cnt] = _normal_chunk(seed, start, cnt, sigma)
+
+    if workers == 1 or len(starts) <= 1:
+        for st in starts:
+            work(st)
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(work, starts))
     return out.reshape(shape)
 
 

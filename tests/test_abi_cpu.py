@@ -1,0 +1,93 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments before touching the device, and its kernel-selection
+logic behaves."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_08145_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "axonn_linear.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(axonn_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_declares_the_three_entry_points():
+    names = declared_functions()
+    for n in ("axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in declared_functions():
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+    assert sorted(B.EXPORTS) == declared_functions()
+
+
+def test_version_and_status_strings():
+    assert B.version() >= 100
+    assert B.status_string(0) == "ok"
+    for code in (-1, -2, -3):
+        assert B.status_string(code) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+ALIGNED = 0x1000  # never dereferenced: every call below must fail validation first
+
+
+@pytest.mark.parametrize("fn", ["axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight"])
+def test_invalid_arguments_are_refused_before_any_launch(fn):
+    f = getattr(B, fn)
+    bad = B.AXONN_ERR_INVALID_ARG
+    kw = dict(stream=0, check=False)
+    assert f(-1, 8, 8, "NN", ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, -1, 8, "NN", ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, -1, "NN", ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(2 ** 31, 8, 8, "NN", ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, 3, ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, -1, ALIGNED, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, "NN", 0, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED, 0, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED, ALIGNED, 0, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED + 2, ALIGNED, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED, ALIGNED + 8, ALIGNED, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED, ALIGNED, ALIGNED + 4, **kw) == bad
+    assert f(8, 8, 8, "NN", ALIGNED, ALIGNED, ALIGNED, fp32_accumulate=2, **kw) == bad
+    # an empty output is fine and touches nothing
+    assert f(0, 8, 8, "NT", 0, 0, 0, **kw) == B.AXONN_OK
+    assert f(8, 0, 8, "TN", 0, 0, 0, **kw) == B.AXONN_OK
+    with pytest.raises(B.AxonnError):
+        f(8, 8, 8, "NN", 0, 0, 0, stream=0)
+
+
+def test_variant_table_and_selection():
+    n = B.num_variants()
+    assert n >= 2 and B.variant_name(0) == "naive"
+    assert B.variant_name(n) is None and B.variant_name(-1) is None
+    names = [B.variant_name(v) for v in range(n)]
+    assert len(set(names)) == n
+    # the guarded kernel takes everything, tile kernels only whole tiles
+    for lay in ("NN", "NT", "TN"):
+        assert B.variant_supports(0, 3, 5, 7, lay)
+        for v in range(1, n):
+            assert not B.variant_supports(v, 100, 200, 300, lay)
+            assert B.variant_supports(v, 1024, 1024, 1024, lay)
+            assert not B.variant_supports(v, 1024, 1024, 1000, lay)
+        # ragged or degenerate shapes go to the guarded kernel, large ones to an MFMA kernel
+        assert B.select_variant(100, 200, 300, lay) == 0
+        assert B.select_variant(256, 256, 0, lay) == 0
+        for shape in [(2048, 12288, 4096), (4096, 16384, 2048), (8192, 8192, 8192), (2048, 8192, 2048)]:
+            v = B.select_variant(*shape, lay)
+            assert v > 0 and B.variant_supports(v, *shape, lay)
+    assert B.select_variant(-1, 8, 8, "NN") == B.AXONN_ERR_INVALID_ARG
+    with pytest.raises(B.AxonnError):
+        B.force_variant(n)
+    B.force_variant(-1)

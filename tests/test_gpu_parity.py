@@ -1,0 +1,237 @@
+"""GPU parity: every result of the HIP library is compared with the CPU oracle on the same
+seeded inputs, through the C ABI (binding.py only marshals arguments).
+
+Tolerance (written here as in tests/gpu_util.py): normwise relative error <= 1e-2 and
+elementwise error <= 2e-2 * max|ref|; integer-valued inputs must match RNE_bf16(ref) bit for
+bit, because every partial sum is then an integer below 2^24 and exact in fp32 under any
+summation order.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_08145_amd import binding as B
+from paper_2502_08145_amd import synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = ["NN", "NT", "TN"]
+OPS = ["fwd", "bwd_data", "bwd_weight"]
+
+
+def store(a_mk, b_kn, layout):
+    if layout == "NN":
+        return a_mk, b_kn
+    if layout == "NT":
+        return a_mk, synth.transpose_bits(b_kn)
+    return synth.transpose_bits(a_mk), b_kn
+
+
+def run_gpu(op, M, N, K, layout, A_bits, B_bits, variant=-1, stream=None, poison=True):
+    a, b = U.to_device(A_bits), U.to_device(B_bits)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    if poison:
+        c.view(torch.int16).fill_(0x7FC0)  # bf16 NaN pattern: unwritten output shows up
+    B.force_variant(variant)
+    try:
+        B.OPS[op](M, N, K, layout, a, b, c, 1, stream)
+    finally:
+        B.force_variant(-1)
+    torch.cuda.synchronize()
+    return U.to_host_bits(c)
+
+
+def tile_variants():
+    return [v for v in range(1, B.num_variants())]
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-test] {request.node.name}", flush=True)
+    yield
+
+
+# ------------------------------------------------------------------ ragged shapes, guarded kernel
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 1, 33), (1, 64, 1), (37, 53, 71), (130, 257, 65)])
+def test_ragged_shapes_any_size(oracle_mod, layout, shape):
+    M, N, K = shape
+    a = synth.normal_bf16(1000 + M, (M, K))
+    b = synth.normal_bf16(2000 + N, (K, N), 0.02)
+    A, Bm = store(a, b, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    assert B.select_variant(M, N, K, layout) == 0
+    for op in OPS:
+        got = run_gpu(op, M, N, K, layout, A, Bm)
+        U.assert_close(got, ref, f"{op} {layout} {shape}")
+
+
+def test_k_zero_gives_zero_and_empty_outputs_are_ok():
+    c = torch.full((8, 16), 3.0, dtype=torch.bfloat16, device="cuda")
+    a = torch.empty((8, 0), dtype=torch.bfloat16, device="cuda")
+    b = torch.empty((0, 16), dtype=torch.bfloat16, device="cuda")
+    B.axonn_linear_fwd(8, 16, 0, "NN", a, b, c)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.to_host_bits(c), np.zeros((8, 16), np.uint16))
+    assert B.axonn_linear_fwd(0, 16, 8, "NN", 0, 0, 0, check=False) == B.AXONN_OK
+
+
+# ------------------------------------------------------------------ every tile kernel, several tiles
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_every_tile_variant_against_oracle(oracle_mod, layout):
+    # 3 x 3 tiles of 256 (6 x 6 of 128), 5 K-steps: multi-tile, odd step count
+    M, N, K = 768, 768, 320
+    a = synth.normal_bf16(31, (M, K))
+    b = synth.normal_bf16(32, (K, N), 0.02)
+    A, Bm = store(a, b, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    for v in tile_variants():
+        assert B.variant_supports(v, M, N, K, layout)
+        got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+        nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+        # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
+        assert nw < 4e-3, (B.variant_name(v), nw)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_single_k_step_and_single_tile(oracle_mod, layout):
+    M, N, K = 256, 256, 64
+    a = synth.normal_bf16(41, (M, K))
+    b = synth.normal_bf16(42, (K, N))
+    A, Bm = store(a, b, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    for v in tile_variants():
+        got = run_gpu("bwd_data", M, N, K, layout, A, Bm, variant=v)
+        U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+
+
+# ------------------------------------------------------------------ exact integers: bit for bit
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_integer_inputs_are_bit_exact(oracle_mod, layout):
+    M, N, K = 512, 768, 448   # rectangular, 7 K-steps, 2x3 tiles of 256
+    a = synth.integer_bf16(51, (M, K), -4, 4)
+    b = synth.integer_bf16(52, (K, N), -4, 4)
+    A, Bm = store(a, b, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    want = U.f64_to_bf16_bits_rne(ref)
+    for v in [0] + tile_variants():
+        got = run_gpu("bwd_weight", M, N, K, layout, A, Bm, variant=v)
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, f"{B.variant_name(v)} {layout}: {len(bad)} mismatches, first at {bad[0]}"
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_position_coded_operands_catch_any_index_slip(oracle_mod, layout):
+    # A is one-hot per row with a row-dependent column, B holds a distinct exact value per
+    # (k, j): C[i, j] = B[sel(i), j], exact in bf16, so any swapped row/column/k shows up.
+    M, N, K = 512, 512, 256
+    sel = (np.arange(M) * 37 + 11) % K
+    a = np.zeros((M, K), np.float32)
+    a[np.arange(M), sel] = 1.0
+    kk, jj = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    b = ((kk % 16) * 16 + (jj % 16) - 128).astype(np.float32) * np.where((kk // 16 + jj // 16) % 2 == 0, 1.0, 0.5)
+    a_bits, b_bits = synth.f32_to_bf16_bits(a).reshape(M, K), synth.f32_to_bf16_bits(b).reshape(K, N)
+    assert np.array_equal(synth.bf16_bits_to_f32(b_bits).reshape(K, N), b)
+    A, Bm = store(a_bits, b_bits, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    assert np.array_equal(ref, b[sel].astype(np.float64))
+    for v in [0] + tile_variants():
+        got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+        assert np.array_equal(U.bits_to_f64(got), ref), f"{B.variant_name(v)} {layout}"
+
+
+# ------------------------------------------------------------------ config 1 in full: tiny GPT MLP
+def test_tiny_mlp_all_ops_all_layouts(oracle_mod):
+    tokens, h, ff = 1024, 512, 2048
+    for tag, (d_in, d_out), seed in (("fc1", (h, ff), 100), ("fc2", (ff, h), 200)):
+        t = synth.fc_layer_tensors(tokens, d_in, d_out, synth.BASE_SEED + seed)
+        for g in synth.fc_layer_gemms(tokens, d_in, d_out, tag):
+            ref = None
+            for layout in LAYOUTS:
+                A, Bm = synth.operands_for(g["op"], layout, t)
+                if ref is None:   # all three modes of one GEMM have the same reference result
+                    ref = oracle_mod.gemm(g["M"], g["N"], g["K"], layout, A, Bm)
+                got = run_gpu(g["op"], g["M"], g["N"], g["K"], layout, A, Bm)
+                U.assert_close(got, ref, f"{g['name']} {layout}")
+
+
+# ------------------------------------------------------------------ determinism, streams, errors
+def test_same_inputs_same_bits_and_side_stream(oracle_mod):
+    M, N, K = 1024, 512, 1024
+    a = synth.normal_bf16(61, (M, K))
+    b = synth.normal_bf16(62, (K, N))
+    first = run_gpu("fwd", M, N, K, "NN", a, b)
+    for _ in range(3):
+        assert np.array_equal(run_gpu("fwd", M, N, K, "NN", a, b), first)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        other = run_gpu("fwd", M, N, K, "NN", a, b, stream=s)
+    assert np.array_equal(other, first)
+
+
+def test_forced_variant_that_cannot_run_is_refused():
+    a = torch.zeros((100, 64), dtype=torch.bfloat16, device="cuda")
+    b = torch.zeros((64, 100), dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros((100, 100), dtype=torch.bfloat16, device="cuda")
+    B.force_variant(1)
+    try:
+        assert B.axonn_linear_fwd(100, 100, 64, "NN", a, b, c, check=False) == B.AXONN_ERR_UNSUPPORTED
+    finally:
+        B.force_variant(-1)
+    assert B.axonn_linear_fwd(100, 100, 64, "NN", a, b, c, check=False) == B.AXONN_OK
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ full benchmark sizes, sampled
+def _sample_positions(M, N, seed, n_rows=4, n_cols=4, block=128):
+    rng = np.random.default_rng(seed)
+    ii, jj = [], []
+    for r in rng.choice(M, size=min(n_rows, M), replace=False):          # full rows
+        ii.append(np.full(N, r)); jj.append(np.arange(N))
+    for c in rng.choice(N, size=min(n_cols, N), replace=False):          # full columns
+        ii.append(np.arange(M)); jj.append(np.full(M, c))
+    bi, bj = np.meshgrid(np.arange(0, M, block), np.arange(0, N, block), indexing="ij")   # one per block
+    ii.append((bi + rng.integers(0, block, bi.shape)).ravel().clip(max=M - 1))
+    jj.append((bj + rng.integers(0, block, bj.shape)).ravel().clip(max=N - 1))
+    return np.concatenate(ii).astype(np.int64), np.concatenate(jj).astype(np.int64)
+
+
+FULL_SIZE = [
+    # (name, tokens, d_in, d_out): layers whose three GEMMs are the benchmark shapes
+    ("gpt5b.qkv", 2048, 4096, 12288),
+    ("gpt5b.fc2", 2048, 16384, 4096),
+    ("gpt80b_shard.fc1", 4096, 2048, 16384),
+    ("gpt320b_skinny.fc1", 2048, 2048, 8192),
+]
+
+
+@pytest.mark.parametrize("name,tokens,d_in,d_out", FULL_SIZE)
+def test_full_size_layers_sampled(oracle_mod, name, tokens, d_in, d_out):
+    """Benchmark-size GEMMs in the launch configuration bench.py times (automatic variant),
+    checked on full rows, full columns and one seeded element per 128x128 block."""
+    t = synth.fc_layer_tensors(tokens, d_in, d_out, synth.BASE_SEED + 300)
+    for g in synth.fc_layer_gemms(tokens, d_in, d_out, name):
+        M, N, K = g["M"], g["N"], g["K"]
+        ii, jj = _sample_positions(M, N, seed=M + N)
+        ref = None
+        for layout in LAYOUTS:
+            A, Bm = synth.operands_for(g["op"], layout, t)
+            if ref is None:
+                ref = oracle_mod.gemm_at(M, N, K, layout, A, Bm, ii, jj)
+            got = run_gpu(g["op"], M, N, K, layout, A, Bm)
+            assert np.isfinite(U.bits_to_f64(got)).all(), f"{g['name']} {layout}: non-finite output"
+            U.assert_close(got[ii, jj], ref, f"{g['name']} {layout}")
+
+
+@pytest.mark.parametrize("n", [4096, 8192])
+def test_square_layout_sweep_sampled(oracle_mod, n):
+    a = synth.normal_bf16(synth.BASE_SEED + 500, (n, n))
+    b = synth.normal_bf16(synth.BASE_SEED + 501, (n, n))
+    ii, jj = _sample_positions(n, n, seed=n, n_rows=2, n_cols=2)
+    ref = oracle_mod.gemm_at(n, n, n, "NN", a, b, ii, jj)
+    for layout in LAYOUTS:
+        A, Bm = store(a, b, layout)
+        got = run_gpu("fwd", n, n, n, layout, A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all()
+        U.assert_close(got[ii, jj], ref, f"square {n} {layout}")
