@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the FC-layer GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one pass over every GEMM of the workload -- forward, backward-data and
+backward-weight of each FC layer, each in its natural mode (NN, NT, TN) -- with all operands
+already resident in HBM.  The default workload is the unsharded GPT-5B-style layer
+(2048 tokens, hidden 4096: QKV, attention output, FC1, FC2 = 12 GEMMs, 2.474 TFLOP per step).
+
+Prints ONE JSON line on stdout: whole-step throughput in TFLOP/s, a `roofline` object for the
+kernel that takes the most time (flops per launch / mean launch duration measured with HIP
+events in the timed region, against the dense bf16 MFMA peak) and a `cpu_baseline` object (the
+CPU oracle timed on a bounded slab of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense bf16 MFMA
+METRIC = "bf16 GEMM TFLOP/s per GPU (fwd+bwd, NN/NT/TN) and % of MFMA peak"
+
+LAYERS = {
+    # workload -> list of (tag, tokens, d_in, d_out)
+    "tiny_mlp": [("fc1", 1024, 512, 2048), ("fc2", 1024, 2048, 512)],
+    "gpt5b_layer": [("qkv", 2048, 4096, 12288), ("attn_out", 2048, 4096, 4096),
+                    ("fc1", 2048, 4096, 16384), ("fc2", 2048, 16384, 4096)],
+    "gpt80b_shard": [("fc1", 4096, 2048, 16384), ("fc2", 4096, 16384, 2048)],
+    "gpt320b_skinny": [("fc1", 2048, 2048, 8192), ("fc2", 2048, 8192, 2048)],
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="gpt5b_layer", choices=sorted(LAYERS))
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
+                 "run with --gpus 1")
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: WORLD_SIZE > 1 is not supported: the path is single-GPU")
+
+    import numpy as np
+    import torch
+
+    from paper_2502_08145_amd import binding as B
+    from paper_2502_08145_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    # ---- synthetic operands, resident in HBM before any timing ---------------------------
+    gemms = []        # dict(name, op, layout, M, N, K, a, b, c, flops, host=(A_bits, B_bits))
+    seed = synth.BASE_SEED + 100 * sorted(LAYERS).index(args.workload)
+    for li, (tag, tokens, d_in, d_out) in enumerate(LAYERS[args.workload]):
+        t = synth.fc_layer_tensors(tokens, d_in, d_out, seed + 10 * li)
+        dev_t = {k: up(v) for k, v in t.items()}
+        for g in synth.fc_layer_gemms(tokens, d_in, d_out, tag):
+            first, second = {"fwd": ("X", "W"), "bwd_data": ("dY", "W"), "bwd_weight": ("X", "dY")}[g["op"]]
+            g = dict(g)
+            g["a"], g["b"] = dev_t[first], dev_t[second]
+            g["c"] = torch.empty((g["M"], g["N"]), dtype=torch.bfloat16, device=dev)
+            g["flops"] = 2.0 * g["M"] * g["N"] * g["K"]
+            g["host"] = (t[first], t[second])
+            g["variant"] = B.variant_name(B.select_variant(g["M"], g["N"], g["K"], g["layout"]))
+            gemms.append(g)
+    step_flops = sum(g["flops"] for g in gemms)
+    log(f"workload {args.workload}: {len(gemms)} GEMMs, {step_flops / 1e12:.3f} TFLOP per step")
+
+    stream = torch.cuda.current_stream()
+
+    def launch(g):
+        B.OPS[g["op"]](g["M"], g["N"], g["K"], g["layout"], g["a"], g["b"], g["c"], 1, stream)
+
+    for _ in range(args.warmup):
+        for g in gemms:
+            launch(g)
+    torch.cuda.synchronize()
+
+    # ---- timed region: K steps; every launch bracketed by HIP events on the launch stream --
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in gemms]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for gi, g in enumerate(gemms):
+            e0, e1 = ev[s][gi]
+            e0.record(stream)
+            launch(g)
+            e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    per = []
+    for gi, g in enumerate(gemms):
+        ms = float(np.mean([ev[s][gi][0].elapsed_time(ev[s][gi][1]) for s in range(args.steps)]))
+        per.append(ms)
+        log(f"  {g['name']:<22s} {g['layout']} M={g['M']:<6d} N={g['N']:<6d} K={g['K']:<6d} {g['variant']:<20s} "
+            f"{ms * 1e3:8.1f} us  {g['flops'] / ms / 1e9:7.1f} TFLOP/s  {g['flops'] / ms / 1e9 / PEAK_BF16_TFLOPS * 100:5.1f}%")
+    for g in gemms:
+        if not torch.isfinite(g["c"].float()).all():
+            sys.exit(f"bench.py: non-finite output in {g['name']}")
+
+    # dominant kernel = the (variant, layout) instance with the largest summed time
+    groups = {}
+    for g, ms in zip(gemms, per):
+        k = f"{g['variant']}/{g['layout']}"
+        d = groups.setdefault(k, dict(ms=0.0, flops=0.0, n=0))
+        d["ms"] += ms; d["flops"] += g["flops"]; d["n"] += 1
+    dom = max(groups, key=lambda k: groups[k]["ms"])
+    achieved = groups[dom]["flops"] / groups[dom]["ms"] / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "kernel": dom,
+                "launches_per_step": groups[dom]["n"],
+                "mean_launch_us": round(groups[dom]["ms"] / groups[dom]["n"] * 1e3, 2),
+                "flops_per_launch": groups[dom]["flops"] / groups[dom]["n"]}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded slab of the same GEMMs --------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        threads = oracle.max_threads()
+
+        def slab(g, rows):
+            A, Bm = g["host"]
+            rows = min(rows, g["M"])
+            A = np.ascontiguousarray(A[:, :rows]) if g["layout"] == "TN" else np.ascontiguousarray(A[:rows])
+            return rows, A, Bm
+
+        def run(rows):
+            fl, t = 0.0, 0.0
+            for g in gemms:
+                r, A, Bm = slab(g, rows)
+                s = time.perf_counter()
+                oracle.gemm(r, g["N"], g["K"], g["layout"], A, Bm, threads)
+                t += time.perf_counter() - s
+                fl += 2.0 * r * g["N"] * g["K"]
+            return fl, t
+        fl, t = run(threads)               # calibration: one row per thread
+        rows = int(max(threads, min(512, threads * round(args.cpu_seconds / max(t, 1e-3)))))
+        rows -= rows % threads
+        fl, t = run(rows)
+        cpu = {"value": round(fl / t / 1e12, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+               "sample": f"first {rows} output rows of each of the {len(gemms)} GEMMs ({fl / 1e9:.1f} GFLOP, {t:.1f} s)"}
+        log(f"cpu oracle: {fl / t / 1e9:.2f} GFLOP/s on {threads} threads")
+
+    out = {"metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "gemms": len(gemms), "layouts": "natural (fwd NN, bwd_data NT, bwd_weight TN)",
+                      "step_tflop": round(step_flops / 1e12, 4)},
+           "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
