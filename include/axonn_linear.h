@@ -46,7 +46,7 @@
  *   sizes      M, N, K >= 0, each below 2^31, and each operand below 2^40 elements.
  *              M == 0 or N == 0: nothing to do, AXONN_OK.  K == 0: the output is
  *              set to +0.  Any M, N, K is computed correctly; the fast tiled
- *              kernels need M and N to be multiples of 128 and K of 64, other
+ *              kernels need M, N and K to be multiples of 128, other
  *              shapes take a slower guarded kernel.
  *   errors     the return value is AXONN_OK (0) or a negative code below; on an
  *              error nothing has been launched.  No exceptions, no aborts.
@@ -104,7 +104,7 @@ int axonn_linear_version(void);
 /* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any
  * shape; the others are MFMA tile kernels.  Host-only queries: no GPU is touched. */
 int axonn_linear_num_variants(void);
-/* Name such as "mfma_256x256_w2x2"; NULL if `variant` is out of range. */
+/* Name such as "mfma_256x256"; NULL if `variant` is out of range. */
 const char *axonn_linear_variant_name(int variant);
 /* 1 if `variant` can run (M,N,K,layout), else 0. */
 int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout);

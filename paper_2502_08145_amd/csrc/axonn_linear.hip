@@ -44,23 +44,20 @@ struct Variant {
     tile_kernel_t fn[3];             // per layout
 };
 
-#define AXONN_TILE_VARIANT(BM, BN, WM, WN)                                                   \
+#define AXONN_TILE_VARIANT(BM, BN)                                                           \
     {                                                                                        \
-        "mfma_" #BM "x" #BN "_w" #WM "x" #WN, BM, BN, WM* WN * 64,                           \
-            TileCfg<BM, BN, WM, WN>::LDS_BYTES, {                                            \
-            gemm_tile_kernel<BM, BN, WM, WN, true, false>,                                   \
-                gemm_tile_kernel<BM, BN, WM, WN, true, true>,                                \
-                gemm_tile_kernel<BM, BN, WM, WN, false, false>                               \
+        "mfma_" #BM "x" #BN, BM, BN, TileCfg<BM, BN>::NT, TileCfg<BM, BN>::LDS_BYTES, {      \
+            gemm_tile_kernel<BM, BN, true, false>, gemm_tile_kernel<BM, BN, true, true>,     \
+                gemm_tile_kernel<BM, BN, false, false>                                       \
         }                                                                                    \
     }
 
 static const Variant g_variants[] = {
     {"naive", 0, 0, 256, 0, {nullptr, nullptr, nullptr}},
-    AXONN_TILE_VARIANT(256, 256, 2, 2),
-    AXONN_TILE_VARIANT(256, 256, 2, 4),
-    AXONN_TILE_VARIANT(256, 128, 2, 2),
-    AXONN_TILE_VARIANT(128, 256, 2, 2),
-    AXONN_TILE_VARIANT(128, 128, 2, 2),
+    AXONN_TILE_VARIANT(256, 256),
+    AXONN_TILE_VARIANT(256, 128),
+    AXONN_TILE_VARIANT(128, 256),
+    AXONN_TILE_VARIANT(128, 128),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -72,27 +69,34 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
-    return M % var.bm == 0 && N % var.bn == 0 && K % BK == 0;
+    return M % var.bm == 0 && N % var.bn == 0 && K % KUNROLL == 0;
 }
 
-// MI355X has 256 compute units; a grid of fewer tiles than that leaves units idle, and the last
-// partial wave of tiles costs a whole tile time.  Pick the tile shape with the best modelled
-// time: (waves of tiles over 256 CUs) x (tile area) / (per-shape efficiency).
+// Tile-shape choice.  MI355X has 256 compute units; a partly filled last round of tiles costs a
+// whole tile time, and a smaller tile moves more operand bytes per flop.  Pick the variant with the smallest modelled
+// time: rounds x tile area / efficiency, where the efficiencies are throughputs measured on
+// MI355X with every CU busy (8192^3, N(0,1) data), relative to the 256x256 tile of each layout.
+// K-contiguous operands are the dearer ones to stage (64-byte row segments per load), which is
+// why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout) {
-    static const struct { int v; double eff; } cand[] = {{1, 1.00}, {3, 0.85}, {4, 0.85}, {5, 0.70}};
+    static const double eff[3][5] = {
+        /* variant:   naive 256x256 256x128 128x256 128x128 */
+        /* NN */ {0.0, 1.00, 0.78, 0.90, 0.72},
+        /* NT */ {0.0, 1.00, 0.74, 0.75, 0.68},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.75},
+    };
     int best = 0;
     double best_t = 0;
-    for (const auto& c : cand) {
-        if (!variant_supports(c.v, M, N, K, layout)) continue;
-        const Variant& var = g_variants[c.v];
+    for (int v = 1; v < kNumVariants; ++v) {
+        if (!variant_supports(v, M, N, K, layout)) continue;
+        const Variant& var = g_variants[v];
         const int64_t tiles = (M / var.bm) * (N / var.bn);
-        // workgroups resident per CU is limited by LDS (160 KB per CU)
-        const int per_cu = var.lds_bytes > 80 * 1024 ? 1 : 2;
-        const int64_t slots = 256 * per_cu;
-        const int64_t waves = (tiles + slots - 1) / slots;
-        const double t = (double)waves * var.bm * var.bn * per_cu / c.eff;
+        // Every CU works through ceil(tiles / 256) tiles (two small tiles resident on one CU run
+        // side by side at half speed each, which comes to the same).
+        const int64_t rounds = (tiles + 255) / 256;
+        const double t = (double)rounds * var.bm * var.bn / eff[layout][v];
         if (best == 0 || t < best_t) {
-            best = c.v;
+            best = v;
             best_t = t;
         }
     }

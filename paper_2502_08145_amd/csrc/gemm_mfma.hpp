@@ -1,29 +1,49 @@
-// bf16 x bf16 -> fp32 -> bf16 GEMM tile kernels for gfx950 (CDNA4), one output tile per workgroup.
+// bf16 x bf16 -> fp32 -> bf16 GEMM tile kernel for gfx950 (CDNA4): one output tile per workgroup.
 //
-// C[M,N] = sum_k a(i,k) b(k,j)   (the local matrix multiply of Algorithm 1 lines 3, 11, 13)
+//   C[M,N] = sum_k a(i,k) b(k,j)      (the local matrix multiply of Algorithm 1 lines 3, 11, 13)
 //
-// Design, in the order data moves:
-//  * Each operand is either "K-contiguous" in global memory (A of NN/NT, B of NT) or
-//    "MN-contiguous" (A of TN, B of NN/TN).  Whatever it is in global memory, the tile lands
-//    in LDS in ONE canonical form: row r = the m (or n) index, 64 consecutive k as 128 bytes,
-//    split into eight 16-byte chunks whose position inside the row is XOR-swizzled with
-//    (r ^ r>>3) & 7.  A K-contiguous operand is copied chunk by chunk; an MN-contiguous one is
-//    read as 8x8 element blocks (eight 16-byte loads along m for eight consecutive k) and
-//    transposed in registers before the store.  The main loop is therefore identical for NN,
-//    NT and TN.
-//  * The matrix instruction is v_mfma_f32_32x32x16_bf16: lane l supplies, for row l%32, the
-//    eight k values 8*(l/32)..+7 -- exactly one swizzled 16-byte LDS chunk (ds_read_b128).
-//  * The products are issued as mfma(Bfrag, Afrag): the 32x32 result block then holds, in lane
-//    l, column m = l%32 and FOUR CONSECUTIVE n per accumulator quad, so the epilogue can pack
-//    4 bf16 into one 8-byte LDS store, transpose the tile through LDS and write C with
-//    16-byte, fully coalesced global stores.
-//  * LDS is double buffered: global loads for K-step t+1 are issued before the MFMAs of step
-//    t and written to the other buffer afterwards; one barrier per K-step.
+// How the kernel is put together, in the order data moves:
+//
+//  * 4 waves (one per SIMD) own a BM x BN output tile as a 2 x 2 grid of (BM/2) x (BN/2) wave
+//    tiles; the accumulators (up to 256 fp32 per lane) never leave the register file.
+//  * K is consumed 32 at a time.  The operand panels of a K-step live in one of FOUR LDS stages
+//    (a ring); the panels of step t+3 are fetched while step t is multiplied.  Global memory goes
+//    STRAIGHT into LDS (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging, no LDS store
+//    instruction); the loads of a stage are spread over a whole K-step, a few per cluster.
+//  * An operand is either "K-contiguous" in global memory (A of NN/NT, B of NT) or
+//    "MN-contiguous" (A of TN, B of NN/TN):
+//      - K-contiguous panels sit in LDS as rows of 32 k (64 bytes) with the four 16-byte chunks
+//        of a row XOR-swizzled by (row>>2)&3, and are read with ds_read_b128: lane l gets, for
+//        row l%32, the eight k values 8*(l/32)..+7 that v_mfma_f32_32x32x16_bf16 wants.
+//      - MN-contiguous panels sit in LDS exactly as in memory, one LDS row per k, with the 16-byte
+//        chunks of k-row k XOR-swizzled by 4*(k&3), and are read with the transposing
+//        ds_read_b64_tr_b16 (two per fragment).  No register transposes anywhere.
+//    Both swizzles make every read conflict-free on the 64-bank LDS, and because a direct load
+//    writes 1 KB of consecutive LDS per wave the swizzle is applied by choosing WHICH 16 bytes of
+//    global memory each lane fetches.
+//  * The main loop is scheduled by hand.  Measurements on MI355X show that one wave per SIMD
+//    loses about six matrix-pipe cycles for every interruption of a run of MFMAs, whatever the
+//    interruption is, so all non-MFMA work of a half K-step (fragment reads, direct loads) is
+//    issued in two clusters, and the loop contains no address arithmetic at all: every LDS
+//    address is a precomputed VGPR plus an immediate, every global address a precomputed SGPR
+//    base plus one VGPR offset that advances once per K-step.  Loads and LDS reads are inline
+//    asm (the compiler would otherwise re-derive addresses with VALU instructions and pick the
+//    64-bit-VGPR addressing form); the waits on them are therefore written out by hand too.
+//  * One barrier per K-step, placed in the MIDDLE of the step's MFMAs: by then the next stage has
+//    landed (vmcnt) and this stage's last fragments are in registers, so the barrier both
+//    publishes stage t+1 and releases stage t for the loads of step t+4.
+//  * MFMAs are issued as mfma(Bfrag, Afrag): the 32x32 result block then holds, in lane l, column
+//    m = l%32 and FOUR CONSECUTIVE n per accumulator quad, so the epilogue packs 4 bf16 into one
+//    8-byte LDS store, transposes the tile through LDS and writes C with 16-byte coalesced
+//    stores.  fp32 -> bf16 is round-to-nearest-even, once.
 //  * Workgroup ids are remapped so that each of the 8 XCDs (which receive consecutive ids
 //    round-robin and have private L2s) works on a compact patch of output tiles.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
+#include <utility>
 
 namespace axonn {
 
@@ -32,10 +52,22 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 64;          // k extent of one LDS stage
-constexpr int ROW_BYTES = 128;  // BK bf16
+constexpr int KB = 32;                // k per LDS stage
+constexpr int NSTAGE = 4;             // stages in the LDS ring
+constexpr int KUNROLL = KB * NSTAGE;  // K must be a multiple of this (128)
 
-__device__ __forceinline__ uint32_t swz(uint32_t row) { return (row ^ (row >> 3)) & 7u; }
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(Int<Is>{}), ...);
+}
+// f(Int<0>{}), f(Int<1>{}), ... f(Int<N-1>{}): indices usable as template arguments
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs; overflow rounds to inf).
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
@@ -47,153 +79,194 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
 }
 
-// ------------------------------------------------------------------------------------------
-// Global -> register -> LDS staging of one operand tile (ROWS x 64 k).
-// Every global address is (wave-uniform base) + (32-bit per-thread byte offset that never
-// changes), so the loop advances only scalar registers.
-// ------------------------------------------------------------------------------------------
-__device__ __forceinline__ u32x4 ld_global_16(const uint8_t* uniform_base, uint32_t voff) {
-    return *reinterpret_cast<const u32x4*>(uniform_base + voff);
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(size_t)((__attribute__((address_space(3))) const uint8_t*)p);
 }
 
-template <int ROWS, int NT, bool KCONTIG>
-struct TileLoader;
+// One wave-level direct load: lane l fetches 16 bytes at base + voff and they land in LDS at
+// lds_dst + 16*l (lds_dst and base wave-uniform).  M0 carries the LDS address; the s_nop covers
+// the M0-write -> LDS-DMA hazard.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void direct_load16(uint32_t lds_dst, const uint8_t* base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(lds_dst) : "memory", "m0");
+}
+template <int IMM>
+__device__ __forceinline__ void lds_read128(u32x4& dst, uint32_t addr) {
+    static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset is 16 bits");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(IMM));
+}
+template <int IMM>
+__device__ __forceinline__ void lds_read64_tr(u32x2& dst, uint32_t addr) {
+    static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset is 16 bits");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(IMM));
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-// K-contiguous: P[row * ld + k].  Thread t handles chunks t, t+NT, ...; chunk = (row, ck):
-// eight consecutive lanes cover the 128 contiguous bytes of one row.
-template <int ROWS, int NT>
-struct TileLoader<ROWS, NT, true> {
-    static constexpr int CH = (ROWS * 8) / NT;
-    static constexpr int NLOADS = CH, NSTORES = CH;
-    static_assert(CH >= 1 && (ROWS * 8) % NT == 0, "tile/threads mismatch");
-    // Pass c handles rows row + c*NT/8.  With NT a multiple of 256 that adds a multiple of 4 to
-    // row>>3, i.e. flips bit 2 of swz(row) for odd multiples and nothing else: an XOR constant.
-    static_assert(NT % 256 == 0, "swizzle of later passes assumes NT/8 is a multiple of 32");
-    __device__ __forceinline__ static constexpr uint32_t pass_xor(int c) { return ((c * (NT / 64)) & 7) << 4; }
-    u32x4 reg[CH];
-    uint32_t voff, lds_off;
-    uint32_t pass_bytes;  // uniform: global distance between the rows of two passes
+// All LDS reads issued so far have landed.  The fragment registers are made to depend on the wait
+// so that no MFMA reading them can be scheduled above it.
+template <int MI, int NI>
+__device__ __forceinline__ void wait_lds_reads(u32x4* fa, u32x4* fb) {
+    static_assert((MI == 2 || MI == 4) && (NI == 2 || NI == 4), "wave tiles are 2 or 4 blocks a side");
+    if constexpr (MI == 4 && NI == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]),
+                       "+v"(fb[3])::"memory");
+    else if constexpr (MI == 4 && NI == 2)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1])::"memory");
+    else if constexpr (MI == 2 && NI == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3])::"memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1])::"memory");
+}
 
-    __device__ __forceinline__ void init(int t, uint32_t ld_bytes) {
-        const uint32_t row = t >> 3, ck = t & 7;
-        voff = row * ld_bytes + ck * 16;
-        pass_bytes = (NT / 8) * ld_bytes;
-        lds_off = row * ROW_BYTES + ((ck ^ swz(row)) << 4);
-    }
-    __device__ __forceinline__ void load(const uint8_t* tile) {
+// ------------------------------------------------------------------------------------------------
+// Operand policies.  ROWS = tile extent along m (or n); REGION = byte offset of the operand's
+// panel inside a stage; STAGE_BYTES = size of a whole stage.  Each policy gives
+//   init(...)                       per-lane / per-wave constants
+//   issue<C, STAGE>()               the C-th of QL direct loads of this wave into stage STAGE
+//   advance()                       move the global window one K-step on
+//   read<I, S, STAGE>(frag)         fragment of 32-row block I, k16 substep S (0/1) of the stage
+// ------------------------------------------------------------------------------------------------
+template <int ROWS, int REGION, int STAGE_BYTES>
+struct OperandKContig {   // global P[row * ld + k]
+    static constexpr int QL = ROWS / 16 / 4;   // a load covers 16 rows x 64 B
+    static constexpr int NB = ROWS / 2 / 32;   // 32-row blocks per wave tile
+    const uint8_t* base[QL];                   // uniform: first row of each load, k = 0
+    uint32_t voff;                             // per lane: row-in-load * ld + fetched chunk * 16
+    uint32_t lds_dst[QL];                      // uniform: destination inside stage 0
+    uint32_t raddr[2][2];                      // [stage >> 1][substep]: read address of block 0
+
+    __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
+                                         uint32_t lds0, int wave_row_base) {
+        const uint8_t* origin = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * ld_bytes;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) reg[c] = ld_global_16(tile + (size_t)c * pass_bytes, voff);
-    }
-    __device__ __forceinline__ void store(uint8_t* lds) const {
+        for (int c = 0; c < QL; ++c) {
+            base[c] = origin + (size_t)(16 * (wave * QL + c)) * ld_bytes;
+            lds_dst[c] = lds0 + REGION + (wave * QL + c) * 1024;
+        }
+        // lane -> LDS slot (row = lane>>2, slot = lane&3); that slot holds chunk slot ^ ((row>>2)&3)
+        voff = (lane >> 2) * ld_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        // reader: row = wave_row_base + 32*I + lane%32 ((row>>2)&3 does not depend on I),
+        // chunk = 2*S + lane/32
+        const uint32_t row = wave_row_base + (lane & 31);
+        const uint32_t a0 = lds0 + REGION + row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
 #pragma unroll
-        for (int c = 0; c < CH; ++c)
-            *reinterpret_cast<u32x4*>(lds + (lds_off ^ pass_xor(c)) + c * (NT / 8) * ROW_BYTES) = reg[c];
+        for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) raddr[hi][s] = (a0 ^ (s << 5)) + hi * 2 * STAGE_BYTES;
     }
-    __device__ __forceinline__ static size_t kstep_bytes(uint32_t) { return BK * 2; }
+    template <int C, int STAGE>
+    __device__ __forceinline__ void issue() const {
+        direct_load16(lds_dst[C] + STAGE * STAGE_BYTES, base[C], voff);
+    }
+    __device__ __forceinline__ void advance() { voff += KB * 2; }
+    template <int I, int S, int STAGE>
+    __device__ __forceinline__ void read(u32x4& f) const {
+        lds_read128<(STAGE & 1) * STAGE_BYTES + I * 2048>(f, raddr[STAGE >> 1][S]);
+    }
 };
 
-// MN-contiguous: P[k * ld + row].  Thread t handles 8x8 element blocks; block = (mb, kb):
-// lanes 0..7 take 8 consecutive m-blocks (128 contiguous bytes for each k), lane/8 picks kb.
-template <int ROWS, int NT>
-struct TileLoader<ROWS, NT, false> {
-    static constexpr int BLOCKS = ROWS;  // (ROWS/8) m-blocks x 8 k-blocks
-    static constexpr int NB = (BLOCKS + NT - 1) / NT;
-    static constexpr bool PARTIAL = (BLOCKS % NT) != 0;  // only the first BLOCKS threads work
-    static constexpr int NLOADS = 8 * NB, NSTORES = 8 * NB;
-    static_assert(BLOCKS % 64 == 0, "whole waves only");
-    static_assert(!PARTIAL || NB == 1, "partial pass only when there is a single pass");
-    u32x4 reg[NB][8];
-    uint32_t voff, lds_off, ld_b;
-    bool active;
+template <int ROWS, int REGION, int STAGE_BYTES>
+struct OperandMNContig {   // global P[k * ld + row]
+    static constexpr int ROWB = ROWS * 2;              // bytes per k-row in LDS
+    static constexpr int KR = 1024 / ROWB;             // k-rows per load: 2 (256 rows) or 4 (128 rows)
+    static constexpr int QL = KB / KR / 4;
+    static constexpr int NB = ROWS / 2 / 32;
+    static constexpr int CPR = ROWB / 16;              // 16-byte chunks per k-row
+    static_assert(ROWS == 128 || ROWS == 256, "tile extents are 128 or 256");
+    const uint8_t* base[QL];
+    uint32_t voff[2];          // even / odd load index (the k&3 of the rows they carry differs)
+    uint32_t kstep_bytes;
+    uint32_t lds_dst[QL];
+    uint32_t raddr[2][NB];     // [stage >> 1][block]: read address for substep 0, first four k
 
-    __device__ __forceinline__ void init(int t, uint32_t ld_bytes) {
-        const uint32_t mb = (t & 7) | ((t >> 6) << 3), kb = (t >> 3) & 7;
-        ld_b = ld_bytes;
-        voff = kb * 8 * ld_bytes + mb * 16;
-        active = !PARTIAL || t < BLOCKS;
-        // row = mb*8 + i: swz(row) = (i ^ mb) & 7, so store i goes to chunk kb ^ ((i ^ mb) & 7)
-        lds_off = mb * 8 * ROW_BYTES;
-        kb_ = kb;
-        mb_ = mb;
-    }
-    __device__ __forceinline__ void load(const uint8_t* tile) {
-        if (!active) return;  // wave-uniform
+    __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
+                                         uint32_t lds0, int wave_row_base) {
+        const uint8_t* origin = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * 2;
 #pragma unroll
-        for (int c = 0; c < NB; ++c)
+        for (int c = 0; c < QL; ++c) {
+            const int q = wave * QL + c;               // this load carries k-rows KR*q .. KR*q + KR-1
+            base[c] = origin + (size_t)(KR * q) * ld_bytes;
+            lds_dst[c] = lds0 + REGION + q * 1024;
+        }
+        // lane -> (k-row kr of the load, LDS chunk position lane % CPR); that position holds chunk
+        // pos ^ 4*(k&3).  k = KR*q + kr: for KR == 4, k&3 = kr; for KR == 2, k&3 = 2*(c&1) + kr
+        // (wave*QL is even).
+        const uint32_t kr = lane / CPR, pos = lane % CPR;
+        const uint32_t k3_even = kr, k3_odd = (KR == 2) ? 2 + kr : kr;
+        voff[0] = kr * ld_bytes + ((pos ^ (4 * k3_even)) << 4);
+        voff[1] = kr * ld_bytes + ((pos ^ (4 * k3_odd)) << 4);
+        kstep_bytes = KB * ld_bytes;
+        // reader (transposing read, 16-lane groups): group g = lane/16 covers m-half g&1 and
+        // k-half g>>1; lane s of a group addresses k-row (s>>2) and 4 consecutive m at 4*(s&3).
+        const uint32_t sl = lane & 15, g = lane >> 4, kq = sl >> 2;
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                reg[c][j] = ld_global_16(tile + (size_t)j * ld_b + (size_t)c * (NT / 64) * 128, voff);
-    }
-    __device__ __forceinline__ void store(uint8_t* lds) const {
-        if (!active) return;
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // output row i of the block: element i of each of the eight k-rows
-                u32x4 o;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t x = reg[c][2 * q][i >> 1], y = reg[c][2 * q + 1][i >> 1];
-                    o[q] = (i & 1) ? ((x >> 16) | (y & 0xFFFF0000u)) : ((x & 0xFFFFu) | (y << 16));
-                }
-                // pass c covers m-blocks mb + c*NT/8 (a multiple of 8 further: same swizzle)
-                const uint32_t sw = (kb_ ^ i ^ mb_) & 7;
-                *reinterpret_cast<u32x4*>(lds + lds_off + (c * (NT / 8) * 8 + i) * ROW_BYTES + (sw << 4)) = o;
-            }
+        for (int i = 0; i < NB; ++i) {
+            const uint32_t m = wave_row_base + i * 32 + 16 * (g & 1) + 4 * (sl & 3);
+            const uint32_t a0 = lds0 + REGION + (kq + 8 * (g >> 1)) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
+            raddr[0][i] = a0;
+            raddr[1][i] = a0 + 2 * STAGE_BYTES;
         }
     }
-    __device__ __forceinline__ static size_t kstep_bytes(uint32_t ld_bytes) { return (size_t)BK * ld_bytes; }
-    uint32_t kb_, mb_;
-};
-
-// A run of scheduling groups: NM MFMAs with NR LDS reads, NV global loads and NW LDS writes
-// spread evenly between them (compile-time recursion: the builtin wants literal counts).
-template <int MASK, int N>
-__device__ __forceinline__ void sched_group() {
-    if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
-}
-template <int NM, int NR, int NV, int NW, int I = 0>
-__device__ __forceinline__ void interleave_hint() {
-    if constexpr (I < NM) {
-        sched_group<0x008, 1>();                                          // one MFMA
-        sched_group<0x020, ((I + 1) * NV) / NM - (I * NV) / NM>();        // global loads
-        sched_group<0x100, ((I + 1) * NR) / NM - (I * NR) / NM>();        // LDS reads
-        sched_group<0x200, ((I + 1) * NW) / NM - (I * NW) / NM>();        // LDS writes
-        interleave_hint<NM, NR, NV, NW, I + 1>();
+    template <int C, int STAGE>
+    __device__ __forceinline__ void issue() const {
+        direct_load16(lds_dst[C] + STAGE * STAGE_BYTES, base[C], voff[C & 1]);
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// The tile kernel.
-//   BM x BN output tile, WM x WN waves, each wave a (BM/WM) x (BN/WN) sub-tile of 32x32 blocks.
-//   Requires M % BM == 0, N % BN == 0, K % 64 == 0 (checked on the host).
-// ------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN>
-struct TileCfg {
-    static constexpr int NT = WM * WN * 64;
-    static constexpr int TM = BM / WM, TN = BN / WN;
-    static constexpr int MI = TM / 32, NI = TN / 32;
-    static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
-    static constexpr int EPI_BYTES = BM * BN * 2;
-    static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES) ? 2 * STAGE_BYTES : EPI_BYTES;
-    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be whole 32x32 blocks");
+    __device__ __forceinline__ void advance() {
+        voff[0] += kstep_bytes;
+        voff[1] += kstep_bytes;
+    }
+    template <int I, int S, int STAGE>
+    __device__ __forceinline__ void read(u32x4& f) const {
+        u32x2 lo, hi;   // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
+        lds_read64_tr<(STAGE & 1) * STAGE_BYTES + (16 * S) * ROWB>(lo, raddr[STAGE >> 1][I]);
+        lds_read64_tr<(STAGE & 1) * STAGE_BYTES + (16 * S + 4) * ROWB>(hi, raddr[STAGE >> 1][I]);
+        f[0] = lo[0];
+        f[1] = lo[1];
+        f[2] = hi[0];
+        f[3] = hi[1];
+    }
 };
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+struct TileCfg {
+    static constexpr int NT = 256;
+    static constexpr int TM = BM / 2, TN = BN / 2;          // wave tile
+    static constexpr int MI = TM / 32, NI = TN / 32;        // 32x32 blocks per wave tile
+    static constexpr int STAGE_BYTES = (BM + BN) * KB * 2;  // A panel then B panel
+    static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int EPI_BYTES = BM * BN * 2;
+    static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+    static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256), "tile extents are 128 or 256");
+};
+
+// Requires M % BM == 0, N % BN == 0, K % 128 == 0, K >= 128 (checked on the host).
+template <int BM, int BN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_tile_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int M, int N, int K, int tiles_m, int tiles_n, int group_m) {
-    using Cfg = TileCfg<BM, BN, WM, WN>;
-    constexpr int NT = Cfg::NT, TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI;
+    using Cfg = TileCfg<BM, BN>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, SB = Cfg::STAGE_BYTES;
+    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, SB>, OperandMNContig<BM, 0, SB>>::type;
+    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, SB>,
+                                          OperandMNContig<BN, BM * KB * 2, SB>>::type;
+    constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
+    constexpr int NM = MI * NI;                                // MFMAs per half K-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int t = threadIdx.x;
     const int lane = t & 63;
-    const int wave = t >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- workgroup -> output tile: XCD-contiguous, then grouped along m --------------------
+    // ---- workgroup -> output tile: XCD-contiguous, then grouped along m ------------------------
     int pid = blockIdx.x;
     const int nwg = gridDim.x;
     if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
@@ -206,19 +279,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
     const int tile_n = in_group / gm;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
-    const uint32_t lda_b = 2u * (uint32_t)(A_KC ? K : M);  // leading dimensions in bytes
-    const uint32_t ldb_b = 2u * (uint32_t)(B_KC ? K : N);
-    const uint8_t* pa = reinterpret_cast<const uint8_t*>(A) + (A_KC ? (size_t)m0 * lda_b : (size_t)m0 * 2);
-    const uint8_t* pb = reinterpret_cast<const uint8_t*>(B) + (B_KC ? (size_t)n0 * ldb_b : (size_t)n0 * 2);
-
-    using LoaderA = TileLoader<BM, NT, A_KC>;
-    using LoaderB = TileLoader<BN, NT, B_KC>;
-    LoaderA la;
-    LoaderB lb;
-    la.init(t, lda_b);
-    lb.init(t, ldb_b);
-    constexpr int NLOADS = LoaderA::NLOADS + LoaderB::NLOADS;
-    constexpr int NSTORES = LoaderA::NSTORES + LoaderB::NSTORES;
+    const uint32_t lds0 = lds_address(smem);
+    OpA opa;
+    OpB opb;
+    opa.init(A, m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM);
+    opb.init(B, n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN);
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -228,98 +293,136 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // per-lane fragment addresses inside a stage (bytes), for k-substep 0; substep s flips
-    // chunk bits 1..2, which is XOR (s << 5) on the byte offset.
-    const uint32_t half = lane >> 5, r32 = lane & 31;
-    uint32_t a_off[MI], b_off[NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        const uint32_t row = wm * TM + i * 32 + r32;
-        a_off[i] = row * ROW_BYTES + ((half ^ swz(row)) << 4);
-    }
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const uint32_t row = wn * TN + j * 32 + r32;
-        b_off[j] = BM * ROW_BYTES + row * ROW_BYTES + ((half ^ swz(row)) << 4);
-    }
+    u32x4 fa[2][MI], fb[2][NI];   // fragment double buffer: [k16 substep parity][block]
 
-    // Register double buffer of MFMA operand fragments: the LDS reads of k-substep s+1 are
-    // issued before the MFMAs of substep s, and the last substep of a K-step is issued AFTER
-    // the barrier together with the first reads of the next stage, so neither LDS latency
-    // nor the barrier leaves the matrix pipe without queued work.
-    bf16x8 af[2][MI], bf[2][NI];
-    auto read_frags = [&](const uint8_t* stage, int s, int buf) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-            af[buf][i] = *reinterpret_cast<const bf16x8*>(stage + (a_off[i] ^ (s << 5)));
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-            bf[buf][j] = *reinterpret_cast<const bf16x8*>(stage + (b_off[j] ^ (s << 5)));
+    // Nothing may be scheduled across this point (keeps the hand-made instruction order).
+#define AXONN_FENCE() __builtin_amdgcn_sched_barrier(0)
+    // MFMA number IDX (i-major) of a half K-step, on fragment buffer BUF.
+    auto mfma = [&](auto buf_c, auto idx_c) {
+        constexpr int BUF = decltype(buf_c)::value, I = decltype(idx_c)::value / NI, J = decltype(idx_c)::value % NI;
+        acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[BUF][J]),
+                                                            __builtin_bit_cast(bf16x8, fa[BUF][I]), acc[I][J], 0, 0, 0);
     };
-    auto mfma_block = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][j], af[buf][i], acc[i][j], 0, 0, 0);
+    auto mfma_range = [&](auto buf_c, auto lo_c, auto hi_c) {
+        constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
+        static_for<HI - LO>([&](auto d) { mfma(buf_c, Int<LO + decltype(d)::value>{}); });
     };
-    constexpr int NM = MI * NI, NR = MI + NI;
+    auto wait_fragments = [&](auto buf_c) {
+        constexpr int BUF = decltype(buf_c)::value;
+        wait_lds_reads<MI, NI>(fa[BUF], fb[BUF]);
+    };
+    // Half HALF (0/1) of the fragment reads of (stage STAGE, substep S) into buffer BUF.
+    auto read_cluster = [&](auto half_c, auto s_c, auto stage_c, auto buf_c) {
+        constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, ST = decltype(stage_c)::value;
+        constexpr int BUF = decltype(buf_c)::value;
+        static_for<MI / 2>([&](auto d) {
+            constexpr int I = H * (MI / 2) + decltype(d)::value;
+            opa.template read<I, S, ST>(fa[BUF][I]);
+        });
+        static_for<NI / 2>([&](auto d) {
+            constexpr int J = H * (NI / 2) + decltype(d)::value;
+            opb.template read<J, S, ST>(fb[BUF][J]);
+        });
+    };
+    // Half HALF of one operand's direct loads into stage STAGE.
+    auto load_cluster_a = [&](auto half_c, auto stage_c) {
+        constexpr int H = decltype(half_c)::value, ST = decltype(stage_c)::value;
+        static_for<QA / 2>([&](auto d) { opa.template issue<H * (QA / 2) + decltype(d)::value, ST>(); });
+    };
+    auto load_cluster_b = [&](auto half_c, auto stage_c) {
+        constexpr int H = decltype(half_c)::value, ST = decltype(stage_c)::value;
+        static_for<QB / 2>([&](auto d) { opb.template issue<H * (QB / 2) + decltype(d)::value, ST>(); });
+    };
+    auto load_stage = [&](auto stage_c) {
+        load_cluster_a(Int<0>{}, stage_c);
+        load_cluster_a(Int<1>{}, stage_c);
+        load_cluster_b(Int<0>{}, stage_c);
+        load_cluster_b(Int<1>{}, stage_c);
+        opa.advance();
+        opb.advance();
+    };
 
-    const int KT = K / BK;
-    la.load(pa);
-    lb.load(pb);
-    la.store(smem);
-    lb.store(smem + BM * ROW_BYTES);
-    __syncthreads();
-    read_frags(smem, 0, 0);
+    // ---- prologue: K-steps 0..2 in flight, step 0 visible, its first fragments on their way ----
+    load_stage(Int<0>{});
+    load_stage(Int<1>{});
+    load_stage(Int<2>{});
+    wait_vmcnt<2 * NL>();
+    __builtin_amdgcn_s_barrier();
+    AXONN_FENCE();
+    read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, Int<0>{});
+    read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, Int<0>{});
 
-    for (int kt = 0; kt + 1 < KT; ++kt) {
-        const uint8_t* cur = smem + (kt & 1) * Cfg::STAGE_BYTES;
-        uint8_t* nxt = smem + ((kt + 1) & 1) * Cfg::STAGE_BYTES;
-        pa += LoaderA::kstep_bytes(lda_b);
-        pb += LoaderB::kstep_bytes(ldb_b);
-        // substep 0: global loads of the next K-step ride along
-        la.load(pa);
-        lb.load(pb);
-        read_frags(cur, 1, 1);
-        mfma_block(0);
-        interleave_hint<NM, NR, NLOADS, 0>();
-        __builtin_amdgcn_sched_barrier(0);
-        // substep 1
-        read_frags(cur, 2, 0);
-        mfma_block(1);
-        interleave_hint<NM, NR, 0, 0>();
-        __builtin_amdgcn_sched_barrier(0);  // nothing of the LDS refill may start before here
-        // substep 2: the loaded tile goes to the other LDS stage between the MFMAs
-        read_frags(cur, 3, 1);
-        mfma_block(0);
-        la.store(nxt);
-        lb.store(nxt + BM * ROW_BYTES);
-        // (LDS reads first: a write may not be scheduled above a read it could alias)
-        interleave_hint<NM / 2, NR, 0, 0>();
-        interleave_hint<NM - NM / 2, 0, 0, NSTORES>();
-        __syncthreads();
-        // substep 3 runs after the barrier, next to the first reads of the next stage
-        read_frags(nxt, 0, 0);
-        mfma_block(1);
-        interleave_hint<NM, NR, 0, 0>();
-    }
-    {
-        const uint8_t* cur = smem + ((KT - 1) & 1) * Cfg::STAGE_BYTES;
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            read_frags(cur, s + 1, (s + 1) & 1);
-            mfma_block(s & 1);
-            interleave_hint<NM, NR, 0, 0>();
+    // ---- one K-step on stage S -------------------------------------------------------------
+    //   LOAD: also fetch K-step t+3 into stage S+3.   NEXT: a following K-step exists.
+    //   VM:   direct loads that may still be in flight at the barrier (everything older has
+    //         landed, in particular the whole of K-step t+1).
+    auto step = [&](auto stage_c, auto load_c, auto next_c, auto vm_c) {
+        constexpr int S = decltype(stage_c)::value, SL = (S + 3) & 3, SN = (S + 1) & 3;
+        constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value;
+        constexpr int VM = decltype(vm_c)::value;
+        // first half: MFMAs of substep 0 (buffer 0); substep-1 fragments into buffer 1
+        wait_fragments(Int<0>{});
+        AXONN_FENCE();
+        mfma(Int<0>{}, Int<0>{});
+        AXONN_FENCE();
+        read_cluster(Int<0>{}, Int<1>{}, Int<S>{}, Int<1>{});
+        if constexpr (LOAD) load_cluster_a(Int<0>{}, Int<SL>{});
+        AXONN_FENCE();
+        mfma_range(Int<0>{}, Int<1>{}, Int<NM / 2 + 1>{});
+        AXONN_FENCE();
+        read_cluster(Int<1>{}, Int<1>{}, Int<S>{}, Int<1>{});
+        if constexpr (LOAD) load_cluster_a(Int<1>{}, Int<SL>{});
+        AXONN_FENCE();
+        mfma_range(Int<0>{}, Int<NM / 2 + 1>{}, Int<NM>{});
+        AXONN_FENCE();
+        // middle: the last fragments of stage S are in registers and K-step t+1 has landed
+        wait_fragments(Int<1>{});
+        if constexpr (NEXT) {
+            wait_vmcnt<VM>();
+            __builtin_amdgcn_s_barrier();
         }
-        mfma_block(1);
-        __syncthreads();  // every wave is done reading LDS before the epilogue reuses it
-    }
+        AXONN_FENCE();
+        // second half: MFMAs of substep 1 (buffer 1); first fragments of K-step t+1 into buffer 0
+        mfma(Int<1>{}, Int<0>{});
+        AXONN_FENCE();
+        if constexpr (NEXT) read_cluster(Int<0>{}, Int<0>{}, Int<SN>{}, Int<0>{});
+        if constexpr (LOAD) load_cluster_b(Int<0>{}, Int<SL>{});
+        AXONN_FENCE();
+        mfma_range(Int<1>{}, Int<1>{}, Int<NM / 2 + 1>{});
+        AXONN_FENCE();
+        if constexpr (NEXT) read_cluster(Int<1>{}, Int<0>{}, Int<SN>{}, Int<0>{});
+        if constexpr (LOAD) {
+            load_cluster_b(Int<1>{}, Int<SL>{});
+            opa.advance();
+            opb.advance();
+        }
+        AXONN_FENCE();
+        mfma_range(Int<1>{}, Int<NM / 2 + 1>{}, Int<NM>{});
+        AXONN_FENCE();
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    // in flight at the barrier of a loading step: K-step t+2 (NL loads) and the A part of t+3
+    using VmSteady = Int<NL + QA>;
 
-    // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region ----------
+    const int KT = K / KB;   // a multiple of 4, at least 4
+    for (int kt = 0; kt + 4 < KT; kt += 4) {
+        step(Int<0>{}, Yes{}, Yes{}, VmSteady{});
+        step(Int<1>{}, Yes{}, Yes{}, VmSteady{});
+        step(Int<2>{}, Yes{}, Yes{}, VmSteady{});
+        step(Int<3>{}, Yes{}, Yes{}, VmSteady{});
+    }
+    step(Int<0>{}, Yes{}, Yes{}, VmSteady{});   // fetches the last K-step
+    step(Int<1>{}, No{}, Yes{}, Int<NL>{});
+    step(Int<2>{}, No{}, Yes{}, Int<0>{});
+    step(Int<3>{}, No{}, No{}, Int<0>{});
+    __syncthreads();   // every wave is done with the ring before the epilogue reuses LDS
+
+    // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
     // acc[i][j][4g + e] = C[m = i*32 + l%32][n = j*32 + 8g + 4*(l/32) + e]
-    constexpr int CPR = TN / 8;  // 16-byte chunks per row of the wave tile
-    constexpr uint32_t CMASK = (CPR >= 16 ? 16 : CPR) - 1;
+    constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile (8 or 16)
+    constexpr uint32_t CMASK = CPR - 1;
+    const uint32_t half = lane >> 5, r32 = lane & 31;
     uint8_t* epi = smem + wave * (TM * TN * 2);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -333,7 +436,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
                 v[0] = pack2_bf16(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
                 v[1] = pack2_bf16(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
                 *reinterpret_cast<u32x2*>(epi + row * (TN * 2) + ((chunk ^ (row & CMASK)) << 4) + half * 8) = v;
-                if (g == 3) __builtin_amdgcn_sched_barrier(0);  // keep the conversion block by block
+                if (g == 3) AXONN_FENCE();   // convert block by block: keeps register pressure low
             }
     __syncthreads();
     uint16_t* pc = C + (m0 + wm * TM) * (int64_t)N + n0 + wn * TN;
@@ -344,6 +447,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
         const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
         *reinterpret_cast<u32x4*>(pc + (int64_t)row * N + ch * 8) = v;
     }
+#undef AXONN_FENCE
 }
 
 }  // namespace axonn
