@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--workload", default="gpt5b_layer", choices=sorted(LAYERS))
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="before the timed region, run plain device copies of this many MiB (a kernel of known "
+                         "HBM traffic, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
@@ -88,6 +91,17 @@ def main():
             gemms.append(g)
     step_flops = sum(g["flops"] for g in gemms)
     log(f"workload {args.workload}: {len(gemms)} GEMMs, {step_flops / 1e12:.3f} TFLOP per step")
+
+    if args.calibrate_copy > 0:
+        n = args.calibrate_copy * (1 << 20) // 2
+        src = torch.empty(n, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):          # each reads and writes calibrate_copy MiB
+            B.axonn_linear_copy_probe(src, dst, n * 2, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert torch.equal(dst.view(torch.int16), src.view(torch.int16))
+        log(f"copy calibration: 3 device copies of {args.calibrate_copy} MiB")
+        del src, dst
 
     stream = torch.cuda.current_stream()
 

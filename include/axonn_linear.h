@@ -115,6 +115,12 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout);
  * Returns AXONN_OK or AXONN_ERR_INVALID_ARG.  For tests, tuning and the benchmark. */
 int axonn_linear_force_variant(int variant);
 
+/* Measurement aid: enqueue a plain device copy of `bytes` bytes (a multiple of 16; both DEVICE
+ * pointers 16-byte aligned, not overlapping) on `stream`.  Its HBM traffic is exactly `bytes` read
+ * and `bytes` written, which is what profiler byte counters are scaled against.  Returns AXONN_OK,
+ * AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
+int axonn_linear_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

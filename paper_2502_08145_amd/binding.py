@@ -23,7 +23,7 @@ EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
-    "axonn_linear_force_variant",
+    "axonn_linear_force_variant", "axonn_linear_copy_probe",
 )
 
 _lib = None
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_select_variant.restype = ci
         L.axonn_linear_force_variant.argtypes = [ci]
         L.axonn_linear_force_variant.restype = ci
+        L.axonn_linear_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.axonn_linear_copy_probe.restype = ci
         _lib = L
     return _lib
 
@@ -141,6 +143,14 @@ def axonn_linear_bwd_data(M, N, K, layout, dY, W, dX, fp32_accumulate=1, stream=
 def axonn_linear_bwd_weight(M, N, K, layout, X, dY, dW, fp32_accumulate=1, stream=None, check=True):
     """dW[M,N] = X^T * dY (Algorithm 1 line 13)."""
     return _call("axonn_linear_bwd_weight", M, N, K, layout, X, dY, dW, fp32_accumulate, stream, check)
+
+
+def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):
+    """Plain device copy of nbytes (known HBM traffic: nbytes read + nbytes written)."""
+    rc = lib().axonn_linear_copy_probe(_ptr(src), _ptr(dst), int(nbytes), _stream(stream))
+    if check and rc != AXONN_OK:
+        raise AxonnError(rc, "axonn_linear_copy_probe")
+    return rc
 
 
 OPS = {"fwd": axonn_linear_fwd, "bwd_data": axonn_linear_bwd_data, "bwd_weight": axonn_linear_bwd_weight}

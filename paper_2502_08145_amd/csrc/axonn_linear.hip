@@ -33,6 +33,14 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const uint16_t* __restr
     C[i * N + j] = (uint16_t)f32_to_bf16_rne(acc);
 }
 
+// Plain copy of `n16` 16-byte words: a kernel of exactly known HBM traffic (n16 * 16 bytes read and
+// as many written), used to calibrate profiler byte counters.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                         size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------------------------------
 // Variant table
 // ------------------------------------------------------------------------------------------
@@ -211,6 +219,16 @@ int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, 
 int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
     if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 2) return AXONN_ERR_INVALID_ARG;
     return axonn::select_variant(M, N, K, layout);
+}
+
+int axonn_linear_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst || (bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
+        return AXONN_ERR_INVALID_ARG;
+    if (bytes == 0) return AXONN_OK;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(axonn::copy_probe_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const axonn::u32x4*>(src), static_cast<axonn::u32x4*>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
 
 int axonn_linear_force_variant(int variant) {
