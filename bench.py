@@ -160,6 +160,21 @@ def main():
                 "mean_launch_us": round(groups[dom]["ms"] / groups[dom]["n"] * 1e3, 2),
                 "flops_per_launch": groups[dom]["flops"] / groups[dom]["n"]}
 
+    # ---- context: what the matrix pipes sustain on these operand values with no data movement ----
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    pdata = gemms[0]["a"].reshape(-1)[: 1 << 20]          # N(0,1) activations of the first layer
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    iters = 4000
+    B.axonn_linear_mfma_probe(pdata, 200, cus, sink, stream)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record(stream)
+    B.axonn_linear_mfma_probe(pdata, iters, cus, sink, stream)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    probe_tflops = cus * 4 * iters * 64 * 32768.0 / (p0.elapsed_time(p1) * 1e-3) / 1e12
+    log(f"MFMA-only probe on the same N(0,1) values: {probe_tflops:.1f} TFLOP/s ({cus} CUs, registers only)")
+
     # ---- CPU baseline: the oracle as it stands, on a bounded slab of the same GEMMs --------
     cpu = None
     if not args.no_cpu_baseline:
@@ -196,6 +211,7 @@ def main():
            "config": {"workload": args.workload, "gemms": len(gemms), "layouts": "natural (fwd NN, bwd_data NT, bwd_weight TN)",
                       "step_tflop": round(step_flops / 1e12, 4)},
            "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+           "mfma_only_probe_tflops": round(probe_tflops, 1),
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 

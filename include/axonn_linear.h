@@ -46,7 +46,7 @@
  *   sizes      M, N, K >= 0, each below 2^31, and each operand below 2^40 elements.
  *              M == 0 or N == 0: nothing to do, AXONN_OK.  K == 0: the output is
  *              set to +0.  Any M, N, K is computed correctly; the fast tiled
- *              kernels need M, N and K to be multiples of 128, other
+ *              kernels need M and N to be multiples of 128 and K of 32 (K >= 160), other
  *              shapes take a slower guarded kernel.
  *   errors     the return value is AXONN_OK (0) or a negative code below; on an
  *              error nothing has been launched.  No exceptions, no aborts.
@@ -120,6 +120,16 @@ int axonn_linear_force_variant(int variant);
  * and `bytes` written, which is what profiler byte counters are scaled against.  Returns AXONN_OK,
  * AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
 int axonn_linear_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
+
+/* Measurement aid: the matrix-pipe ceiling for a given operand distribution.  Launches
+ * `workgroups` workgroups of 4 waves; every wave reads 32 operand fragments once from `data`
+ * (DEVICE pointer, 16-byte aligned, at least 128 KiB of bf16 values, the same for all workgroups)
+ * and then issues iters * 64 bf16 MFMAs (32x32x16) on registers only: iters * 64 * 32768 flops per
+ * wave, no memory traffic.  `sink` is a DEVICE pointer to one float (never written in practice).
+ * Time it with events; with one workgroup per compute unit this is what the kernels above could
+ * reach if operands were free.  Returns AXONN_OK, AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
+int axonn_linear_mfma_probe(const void *data, size_t data_bytes, int iters, int workgroups,
+                            void *sink, void *stream);
 
 #ifdef __cplusplus
 }

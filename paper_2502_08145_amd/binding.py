@@ -23,7 +23,7 @@ EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
-    "axonn_linear_force_variant", "axonn_linear_copy_probe",
+    "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
 )
 
 _lib = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_force_variant.restype = ci
         L.axonn_linear_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.axonn_linear_copy_probe.restype = ci
+        L.axonn_linear_mfma_probe.argtypes = [vp, ctypes.c_size_t, ci, ci, vp, vp]
+        L.axonn_linear_mfma_probe.restype = ci
         _lib = L
     return _lib
 
@@ -150,6 +152,15 @@ def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):
     rc = lib().axonn_linear_copy_probe(_ptr(src), _ptr(dst), int(nbytes), _stream(stream))
     if check and rc != AXONN_OK:
         raise AxonnError(rc, "axonn_linear_copy_probe")
+    return rc
+
+
+def axonn_linear_mfma_probe(data, iters, workgroups, sink, stream=None, check=True):
+    """Registers-only MFMA loop on the operand values in `data` (bf16 tensor, >= 128 KiB)."""
+    rc = lib().axonn_linear_mfma_probe(_ptr(data), data.numel() * 2, int(iters), int(workgroups), sink.data_ptr(),
+                                       _stream(stream))
+    if check and rc != AXONN_OK:
+        raise AxonnError(rc, "axonn_linear_mfma_probe")
     return rc
 
 

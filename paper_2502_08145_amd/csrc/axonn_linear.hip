@@ -41,6 +41,41 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Nothing but MFMAs: every wave keeps 16 + 16 operand fragments (read once from `data`) and 16
+// accumulator blocks in registers and issues `iters` x 64 v_mfma_f32_32x32x16_bf16, in the same
+// operand pattern as the 256x256 tile kernel (4 A x 4 B fragments per k16 substep).  It measures the
+// matrix-pipe ceiling for a given operand distribution: on MI355X the sustained clock, and with it
+// this ceiling, depends on how much the operand bits toggle.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict__ data, float* __restrict__ sink,
+                                                         int iters) {
+    bf16x8 a[16], b[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * i]);
+        b[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * (16 + i)]);
+    }
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[s * 4 + j], a[s * 4 + i], acc[i * 4 + j], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    if (t == 12345.678f) sink[0] = t;   // keeps the accumulators live; practically never taken
+}
+
 // ------------------------------------------------------------------------------------------
 // Variant table
 // ------------------------------------------------------------------------------------------
@@ -48,20 +83,21 @@ typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, 
 
 struct Variant {
     const char* name;
-    int bm, bn, threads, lds_bytes;  // bm == 0: the naive kernel
+    int bm, bn, threads, lds_bytes, min_k;  // bm == 0: the naive kernel
     tile_kernel_t fn[3];             // per layout
 };
 
 #define AXONN_TILE_VARIANT(BM, BN)                                                           \
     {                                                                                        \
-        "mfma_" #BM "x" #BN, BM, BN, TileCfg<BM, BN>::NT, TileCfg<BM, BN>::LDS_BYTES, {      \
+        "mfma_" #BM "x" #BN, BM, BN, TileCfg<BM, BN>::NT, TileCfg<BM, BN>::LDS_BYTES,        \
+            TileCfg<BM, BN>::MIN_K, {                                                        \
             gemm_tile_kernel<BM, BN, true, false>, gemm_tile_kernel<BM, BN, true, true>,     \
                 gemm_tile_kernel<BM, BN, false, false>                                       \
         }                                                                                    \
     }
 
 static const Variant g_variants[] = {
-    {"naive", 0, 0, 256, 0, {nullptr, nullptr, nullptr}},
+    {"naive", 0, 0, 256, 0, 0, {nullptr, nullptr, nullptr}},
     AXONN_TILE_VARIANT(256, 256),
     AXONN_TILE_VARIANT(256, 128),
     AXONN_TILE_VARIANT(128, 256),
@@ -77,7 +113,7 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
-    return M % var.bm == 0 && N % var.bn == 0 && K % KUNROLL == 0;
+    return M % var.bm == 0 && N % var.bn == 0 && K % KB == 0 && K >= var.min_k;
 }
 
 // Tile-shape choice.  MI355X has 256 compute units; a partly filled last round of tiles costs a
@@ -228,6 +264,16 @@ int axonn_linear_copy_probe(const void* src, void* dst, size_t bytes, void* stre
     (void)hipGetLastError();
     hipLaunchKernelGGL(axonn::copy_probe_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const axonn::u32x4*>(src), static_cast<axonn::u32x4*>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
+}
+
+int axonn_linear_mfma_probe(const void* data, size_t data_bytes, int iters, int workgroups, void* sink, void* stream) {
+    if (!data || !sink || (reinterpret_cast<uintptr_t>(data) & 15) || data_bytes < 32u * 256u * 16u || iters < 0 ||
+        workgroups < 1 || workgroups > 65536)
+        return AXONN_ERR_INVALID_ARG;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(axonn::mfma_probe_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const axonn::u32x4*>(data), static_cast<float*>(sink), iters);
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
 

@@ -6,8 +6,9 @@
 //
 //  * 4 waves (one per SIMD) own a BM x BN output tile as a 2 x 2 grid of (BM/2) x (BN/2) wave
 //    tiles; the accumulators (up to 256 fp32 per lane) never leave the register file.
-//  * K is consumed 32 at a time.  The operand panels of a K-step live in one of FOUR LDS stages
-//    (a ring); the panels of step t+3 are fetched while step t is multiplied.  Global memory goes
+//  * K is consumed 32 at a time.  The operand panels of a K-step live in one stage of an LDS ring
+//    of NS stages (as many as fit in 160 KB: 5 for the 256x256 tile); the panels of step t+NS-1
+//    are fetched while step t is multiplied.  Global memory goes
 //    STRAIGHT into LDS (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging, no LDS store
 //    instruction); the loads of a stage are spread over a whole K-step, a few per cluster.
 //  * An operand is either "K-contiguous" in global memory (A of NN/NT, B of NT) or
@@ -24,14 +25,14 @@
 //  * The main loop is scheduled by hand.  Measurements on MI355X show that one wave per SIMD
 //    loses about six matrix-pipe cycles for every interruption of a run of MFMAs, whatever the
 //    interruption is, so all non-MFMA work of a half K-step (fragment reads, direct loads) is
-//    issued in two clusters, and the loop contains no address arithmetic at all: every LDS
-//    address is a precomputed VGPR plus an immediate, every global address a precomputed SGPR
+//    issued in two clusters, and the loop contains next to no address arithmetic: an LDS address
+//    is (precomputed VGPR + stage offset) plus an immediate, a global address a precomputed SGPR
 //    base plus one VGPR offset that advances once per K-step.  Loads and LDS reads are inline
 //    asm (the compiler would otherwise re-derive addresses with VALU instructions and pick the
 //    64-bit-VGPR addressing form); the waits on them are therefore written out by hand too.
 //  * One barrier per K-step, placed in the MIDDLE of the step's MFMAs: by then the next stage has
 //    landed (vmcnt) and this stage's last fragments are in registers, so the barrier both
-//    publishes stage t+1 and releases stage t for the loads of step t+4.
+//    publishes stage t+1 and releases stage t for the loads of step t+NS.
 //  * MFMAs are issued as mfma(Bfrag, Afrag): the 32x32 result block then holds, in lane l, column
 //    m = l%32 and FOUR CONSECUTIVE n per accumulator quad, so the epilogue packs 4 bf16 into one
 //    8-byte LDS store, transposes the tile through LDS and writes C with 16-byte coalesced
@@ -52,9 +53,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int KB = 32;                // k per LDS stage
-constexpr int NSTAGE = 4;             // stages in the LDS ring
-constexpr int KUNROLL = KB * NSTAGE;  // K must be a multiple of this (128)
+constexpr int KB = 32;   // k per LDS stage; K must be a multiple of it
 
 template <int V>
 using Int = std::integral_constant<int, V>;
@@ -127,20 +126,25 @@ __device__ __forceinline__ void wait_lds_reads(u32x4* fa, u32x4* fb) {
 
 // ------------------------------------------------------------------------------------------------
 // Operand policies.  ROWS = tile extent along m (or n); REGION = byte offset of the operand's
-// panel inside a stage; STAGE_BYTES = size of a whole stage.  Each policy gives
-//   init(...)                       per-lane / per-wave constants
-//   issue<C, STAGE>()               the C-th of QL direct loads of this wave into stage STAGE
-//   advance()                       move the global window one K-step on
-//   read<I, S, STAGE>(frag)         fragment of 32-row block I, k16 substep S (0/1) of the stage
+// panel inside a stage.  Each policy gives
+//   init(...)                  per-lane / per-wave constants
+//   issue<C>(stage_off)        the C-th of QL direct loads of this wave into the stage at stage_off
+//   advance()                  move the global window one K-step on
+//   cursor(stage_off)          the VGPR addresses for reading that stage (made once per K-step)
+//   read<I, S>(frag, cursor)   fragment of 32-row block I, k16 substep S (0/1)
+// The stage offset is the only run-time part of an LDS address; everything else is an immediate.
 // ------------------------------------------------------------------------------------------------
-template <int ROWS, int REGION, int STAGE_BYTES>
+template <int ROWS, int REGION>
 struct OperandKContig {   // global P[row * ld + k]
     static constexpr int QL = ROWS / 16 / 4;   // a load covers 16 rows x 64 B
     static constexpr int NB = ROWS / 2 / 32;   // 32-row blocks per wave tile
+    struct Cursor {
+        uint32_t a[2];   // [substep]
+    };
     const uint8_t* base[QL];                   // uniform: first row of each load, k = 0
     uint32_t voff;                             // per lane: row-in-load * ld + fetched chunk * 16
     uint32_t lds_dst[QL];                      // uniform: destination inside stage 0
-    uint32_t raddr[2][2];                      // [stage >> 1][substep]: read address of block 0
+    uint32_t raddr[2];                         // [substep]: read address of block 0 in stage 0
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base) {
@@ -156,23 +160,24 @@ struct OperandKContig {   // global P[row * ld + k]
         // chunk = 2*S + lane/32
         const uint32_t row = wave_row_base + (lane & 31);
         const uint32_t a0 = lds0 + REGION + row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
-#pragma unroll
-        for (int hi = 0; hi < 2; ++hi)
-#pragma unroll
-            for (int s = 0; s < 2; ++s) raddr[hi][s] = (a0 ^ (s << 5)) + hi * 2 * STAGE_BYTES;
+        raddr[0] = a0;
+        raddr[1] = a0 ^ 32;
     }
-    template <int C, int STAGE>
-    __device__ __forceinline__ void issue() const {
-        direct_load16(lds_dst[C] + STAGE * STAGE_BYTES, base[C], voff);
+    template <int C>
+    __device__ __forceinline__ void issue(uint32_t stage_off) const {
+        direct_load16(lds_dst[C] + stage_off, base[C], voff);
     }
     __device__ __forceinline__ void advance() { voff += KB * 2; }
-    template <int I, int S, int STAGE>
-    __device__ __forceinline__ void read(u32x4& f) const {
-        lds_read128<(STAGE & 1) * STAGE_BYTES + I * 2048>(f, raddr[STAGE >> 1][S]);
+    __device__ __forceinline__ Cursor cursor(uint32_t stage_off) const {
+        return Cursor{{raddr[0] + stage_off, raddr[1] + stage_off}};
+    }
+    template <int I, int S>
+    __device__ __forceinline__ void read(u32x4& f, const Cursor& c) const {
+        lds_read128<I * 2048>(f, c.a[S]);
     }
 };
 
-template <int ROWS, int REGION, int STAGE_BYTES>
+template <int ROWS, int REGION>
 struct OperandMNContig {   // global P[k * ld + row]
     static constexpr int ROWB = ROWS * 2;              // bytes per k-row in LDS
     static constexpr int KR = 1024 / ROWB;             // k-rows per load: 2 (256 rows) or 4 (128 rows)
@@ -180,11 +185,14 @@ struct OperandMNContig {   // global P[k * ld + row]
     static constexpr int NB = ROWS / 2 / 32;
     static constexpr int CPR = ROWB / 16;              // 16-byte chunks per k-row
     static_assert(ROWS == 128 || ROWS == 256, "tile extents are 128 or 256");
+    struct Cursor {
+        uint32_t a[NB];
+    };
     const uint8_t* base[QL];
     uint32_t voff[2];          // even / odd load index (the k&3 of the rows they carry differs)
     uint32_t kstep_bytes;
     uint32_t lds_dst[QL];
-    uint32_t raddr[2][NB];     // [stage >> 1][block]: read address for substep 0, first four k
+    uint32_t raddr[NB];        // [block]: read address in stage 0 for substep 0, first four k
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base) {
@@ -209,24 +217,28 @@ struct OperandMNContig {   // global P[k * ld + row]
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const uint32_t m = wave_row_base + i * 32 + 16 * (g & 1) + 4 * (sl & 3);
-            const uint32_t a0 = lds0 + REGION + (kq + 8 * (g >> 1)) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
-            raddr[0][i] = a0;
-            raddr[1][i] = a0 + 2 * STAGE_BYTES;
+            raddr[i] = lds0 + REGION + (kq + 8 * (g >> 1)) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
         }
     }
-    template <int C, int STAGE>
-    __device__ __forceinline__ void issue() const {
-        direct_load16(lds_dst[C] + STAGE * STAGE_BYTES, base[C], voff[C & 1]);
+    template <int C>
+    __device__ __forceinline__ void issue(uint32_t stage_off) const {
+        direct_load16(lds_dst[C] + stage_off, base[C], voff[C & 1]);
     }
     __device__ __forceinline__ void advance() {
         voff[0] += kstep_bytes;
         voff[1] += kstep_bytes;
     }
-    template <int I, int S, int STAGE>
-    __device__ __forceinline__ void read(u32x4& f) const {
+    __device__ __forceinline__ Cursor cursor(uint32_t stage_off) const {
+        Cursor c;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) c.a[i] = raddr[i] + stage_off;
+        return c;
+    }
+    template <int I, int S>
+    __device__ __forceinline__ void read(u32x4& f, const Cursor& c) const {
         u32x2 lo, hi;   // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
-        lds_read64_tr<(STAGE & 1) * STAGE_BYTES + (16 * S) * ROWB>(lo, raddr[STAGE >> 1][I]);
-        lds_read64_tr<(STAGE & 1) * STAGE_BYTES + (16 * S + 4) * ROWB>(hi, raddr[STAGE >> 1][I]);
+        lds_read64_tr<(16 * S) * ROWB>(lo, c.a[I]);
+        lds_read64_tr<(16 * S + 4) * ROWB>(hi, c.a[I]);
         f[0] = lo[0];
         f[1] = lo[1];
         f[2] = hi[0];
@@ -235,28 +247,33 @@ struct OperandMNContig {   // global P[k * ld + row]
 };
 
 // ------------------------------------------------------------------------------------------------
+// NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile stays at 64 KB so
+// that two workgroups share a CU).
 template <int BM, int BN>
 struct TileCfg {
     static constexpr int NT = 256;
     static constexpr int TM = BM / 2, TN = BN / 2;          // wave tile
     static constexpr int MI = TM / 32, NI = TN / 32;        // 32x32 blocks per wave tile
     static constexpr int STAGE_BYTES = (BM + BN) * KB * 2;  // A panel then B panel
-    static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int NS = (BM + BN == 512) ? 5 : (BM + BN == 384) ? 6 : 4;
+    static constexpr int RING_BYTES = NS * STAGE_BYTES;
     static constexpr int EPI_BYTES = BM * BN * 2;
     static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+    static constexpr int MIN_K = KB * (NS - 1);             // the prologue fills NS-1 stages
     static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256), "tile extents are 128 or 256");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
-// Requires M % BM == 0, N % BN == 0, K % 128 == 0, K >= 128 (checked on the host).
+// Requires M % BM == 0, N % BN == 0, K % 32 == 0, K >= TileCfg::MIN_K (checked on the host).
 template <int BM, int BN, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int M, int N, int K, int tiles_m, int tiles_n, int group_m) {
     using Cfg = TileCfg<BM, BN>;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, SB = Cfg::STAGE_BYTES;
-    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, SB>, OperandMNContig<BM, 0, SB>>::type;
-    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, SB>,
-                                          OperandMNContig<BN, BM * KB * 2, SB>>::type;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS;
+    constexpr uint32_t SB = Cfg::STAGE_BYTES, RING = Cfg::RING_BYTES;
+    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0>, OperandMNContig<BM, 0>>::type;
+    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2>, OperandMNContig<BN, BM * KB * 2>>::type;
     constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
     constexpr int NM = MI * NI;                                // MFMAs per half K-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -311,53 +328,58 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
         constexpr int BUF = decltype(buf_c)::value;
         wait_lds_reads<MI, NI>(fa[BUF], fb[BUF]);
     };
-    // Half HALF (0/1) of the fragment reads of (stage STAGE, substep S) into buffer BUF.
-    auto read_cluster = [&](auto half_c, auto s_c, auto stage_c, auto buf_c) {
-        constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, ST = decltype(stage_c)::value;
-        constexpr int BUF = decltype(buf_c)::value;
+    // Half HALF (0/1) of the fragment reads of substep S through the given cursors into buffer BUF.
+    auto read_cluster = [&](auto half_c, auto s_c, auto buf_c, const typename OpA::Cursor& ca,
+                            const typename OpB::Cursor& cb) {
+        constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, BUF = decltype(buf_c)::value;
         static_for<MI / 2>([&](auto d) {
             constexpr int I = H * (MI / 2) + decltype(d)::value;
-            opa.template read<I, S, ST>(fa[BUF][I]);
+            opa.template read<I, S>(fa[BUF][I], ca);
         });
         static_for<NI / 2>([&](auto d) {
             constexpr int J = H * (NI / 2) + decltype(d)::value;
-            opb.template read<J, S, ST>(fb[BUF][J]);
+            opb.template read<J, S>(fb[BUF][J], cb);
         });
     };
-    // Half HALF of one operand's direct loads into stage STAGE.
-    auto load_cluster_a = [&](auto half_c, auto stage_c) {
-        constexpr int H = decltype(half_c)::value, ST = decltype(stage_c)::value;
-        static_for<QA / 2>([&](auto d) { opa.template issue<H * (QA / 2) + decltype(d)::value, ST>(); });
+    // Half HALF of one operand's direct loads into the stage at stage_off.
+    auto load_cluster_a = [&](auto half_c, uint32_t stage_off) {
+        constexpr int H = decltype(half_c)::value;
+        static_for<QA / 2>([&](auto d) { opa.template issue<H * (QA / 2) + decltype(d)::value>(stage_off); });
     };
-    auto load_cluster_b = [&](auto half_c, auto stage_c) {
-        constexpr int H = decltype(half_c)::value, ST = decltype(stage_c)::value;
-        static_for<QB / 2>([&](auto d) { opb.template issue<H * (QB / 2) + decltype(d)::value, ST>(); });
+    auto load_cluster_b = [&](auto half_c, uint32_t stage_off) {
+        constexpr int H = decltype(half_c)::value;
+        static_for<QB / 2>([&](auto d) { opb.template issue<H * (QB / 2) + decltype(d)::value>(stage_off); });
     };
-    auto load_stage = [&](auto stage_c) {
-        load_cluster_a(Int<0>{}, stage_c);
-        load_cluster_a(Int<1>{}, stage_c);
-        load_cluster_b(Int<0>{}, stage_c);
-        load_cluster_b(Int<1>{}, stage_c);
+    auto next_stage = [&](uint32_t off) -> uint32_t { return off + SB == RING ? 0u : off + SB; };
+
+    // ---- prologue: K-steps 0..NS-2 in flight, step 0 visible, its first fragments on their way --
+    uint32_t st_load = 0;   // stage that receives the next K-step to be fetched
+    static_for<NS - 1>([&](auto) {
+        load_cluster_a(Int<0>{}, st_load);
+        load_cluster_a(Int<1>{}, st_load);
+        load_cluster_b(Int<0>{}, st_load);
+        load_cluster_b(Int<1>{}, st_load);
         opa.advance();
         opb.advance();
-    };
-
-    // ---- prologue: K-steps 0..2 in flight, step 0 visible, its first fragments on their way ----
-    load_stage(Int<0>{});
-    load_stage(Int<1>{});
-    load_stage(Int<2>{});
-    wait_vmcnt<2 * NL>();
+        st_load += SB;
+    });
+    wait_vmcnt<(NS - 2) * NL>();
     __builtin_amdgcn_s_barrier();
     AXONN_FENCE();
-    read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, Int<0>{});
-    read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, Int<0>{});
+    uint32_t st_cur = 0, st_next = SB;
+    // read cursors of the current stage; the ones of the next stage are made in the second half of
+    // a step and become the current ones when the step ends
+    typename OpA::Cursor ca = opa.cursor(st_cur);
+    typename OpB::Cursor cb = opb.cursor(st_cur);
+    read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
+    read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
 
-    // ---- one K-step on stage S -------------------------------------------------------------
-    //   LOAD: also fetch K-step t+3 into stage S+3.   NEXT: a following K-step exists.
+    // ---- one K-step on the stage at st_cur ---------------------------------------------------
+    //   LOAD: also fetch K-step t+NS-1 into the stage at st_load (the one step t-1 used).
+    //   NEXT: a following K-step exists.
     //   VM:   direct loads that may still be in flight at the barrier (everything older has
     //         landed, in particular the whole of K-step t+1).
-    auto step = [&](auto stage_c, auto load_c, auto next_c, auto vm_c) {
-        constexpr int S = decltype(stage_c)::value, SL = (S + 3) & 3, SN = (S + 1) & 3;
+    auto step = [&](auto load_c, auto next_c, auto vm_c) {
         constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value;
         constexpr int VM = decltype(vm_c)::value;
         // first half: MFMAs of substep 0 (buffer 0); substep-1 fragments into buffer 1
@@ -365,17 +387,17 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
         AXONN_FENCE();
         mfma(Int<0>{}, Int<0>{});
         AXONN_FENCE();
-        read_cluster(Int<0>{}, Int<1>{}, Int<S>{}, Int<1>{});
-        if constexpr (LOAD) load_cluster_a(Int<0>{}, Int<SL>{});
+        read_cluster(Int<0>{}, Int<1>{}, Int<1>{}, ca, cb);
+        if constexpr (LOAD) load_cluster_a(Int<0>{}, st_load);
         AXONN_FENCE();
         mfma_range(Int<0>{}, Int<1>{}, Int<NM / 2 + 1>{});
         AXONN_FENCE();
-        read_cluster(Int<1>{}, Int<1>{}, Int<S>{}, Int<1>{});
-        if constexpr (LOAD) load_cluster_a(Int<1>{}, Int<SL>{});
+        read_cluster(Int<1>{}, Int<1>{}, Int<1>{}, ca, cb);
+        if constexpr (LOAD) load_cluster_a(Int<1>{}, st_load);
         AXONN_FENCE();
         mfma_range(Int<0>{}, Int<NM / 2 + 1>{}, Int<NM>{});
         AXONN_FENCE();
-        // middle: the last fragments of stage S are in registers and K-step t+1 has landed
+        // middle: the last fragments of this stage are in registers and K-step t+1 has landed
         wait_fragments(Int<1>{});
         if constexpr (NEXT) {
             wait_vmcnt<VM>();
@@ -385,37 +407,37 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
         // second half: MFMAs of substep 1 (buffer 1); first fragments of K-step t+1 into buffer 0
         mfma(Int<1>{}, Int<0>{});
         AXONN_FENCE();
-        if constexpr (NEXT) read_cluster(Int<0>{}, Int<0>{}, Int<SN>{}, Int<0>{});
-        if constexpr (LOAD) load_cluster_b(Int<0>{}, Int<SL>{});
+        if constexpr (NEXT) {
+            ca = opa.cursor(st_next);
+            cb = opb.cursor(st_next);
+            read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
+        }
+        if constexpr (LOAD) load_cluster_b(Int<0>{}, st_load);
         AXONN_FENCE();
         mfma_range(Int<1>{}, Int<1>{}, Int<NM / 2 + 1>{});
         AXONN_FENCE();
-        if constexpr (NEXT) read_cluster(Int<1>{}, Int<0>{}, Int<SN>{}, Int<0>{});
+        if constexpr (NEXT) read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
         if constexpr (LOAD) {
-            load_cluster_b(Int<1>{}, Int<SL>{});
+            load_cluster_b(Int<1>{}, st_load);
             opa.advance();
             opb.advance();
         }
         AXONN_FENCE();
         mfma_range(Int<1>{}, Int<NM / 2 + 1>{}, Int<NM>{});
         AXONN_FENCE();
+        st_load = st_cur;   // the stage just finished is the next one to refill
+        st_cur = st_next;
+        st_next = next_stage(st_next);
     };
     using Yes = std::true_type;
     using No = std::false_type;
-    // in flight at the barrier of a loading step: K-step t+2 (NL loads) and the A part of t+3
-    using VmSteady = Int<NL + QA>;
 
-    const int KT = K / KB;   // a multiple of 4, at least 4
-    for (int kt = 0; kt + 4 < KT; kt += 4) {
-        step(Int<0>{}, Yes{}, Yes{}, VmSteady{});
-        step(Int<1>{}, Yes{}, Yes{}, VmSteady{});
-        step(Int<2>{}, Yes{}, Yes{}, VmSteady{});
-        step(Int<3>{}, Yes{}, Yes{}, VmSteady{});
-    }
-    step(Int<0>{}, Yes{}, Yes{}, VmSteady{});   // fetches the last K-step
-    step(Int<1>{}, No{}, Yes{}, Int<NL>{});
-    step(Int<2>{}, No{}, Yes{}, Int<0>{});
-    step(Int<3>{}, No{}, No{}, Int<0>{});
+    const int KT = K / KB;   // at least NS - 1
+    // steady state: in flight at the barrier are K-steps t+2 .. t+NS-2 and the A part of t+NS-1
+    for (int kt = 0; kt + (NS - 1) < KT; ++kt) step(Yes{}, Yes{}, Int<(NS - 3) * NL + QA>{});
+    // drain: nothing left to fetch; K-steps t+2 .. KT-1 may still be in flight at the barrier
+    static_for<NS - 2>([&](auto j) { step(No{}, Yes{}, Int<(NS - 3 - decltype(j)::value) * NL>{}); });
+    step(No{}, No{}, Int<0>{});
     __syncthreads();   // every wave is done with the ring before the epilogue reuses LDS
 
     // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------

@@ -81,8 +81,9 @@ def test_variant_table_and_selection():
             assert not B.variant_supports(v, 100, 200, 300, lay)
             assert B.variant_supports(v, 1024, 1024, 1024, lay)
             assert not B.variant_supports(v, 1024, 1024, 1000, lay)
-            assert not B.variant_supports(v, 1024, 1024, 192, lay)     # K must be a multiple of 128
-            assert B.variant_supports(v, 256, 256, 128, lay)
+            assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 32
+            assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
+            assert B.variant_supports(v, 256, 256, 160, lay)
         # ragged or degenerate shapes go to the guarded kernel, large ones to an MFMA kernel
         assert B.select_variant(100, 200, 300, lay) == 0
         assert B.select_variant(256, 256, 0, lay) == 0

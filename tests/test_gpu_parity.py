@@ -80,8 +80,8 @@ def test_k_zero_gives_zero_and_empty_outputs_are_ok():
 # ------------------------------------------------------------------ every tile kernel, several tiles
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_every_tile_variant_against_oracle(oracle_mod, layout):
-    # 3 x 3 tiles of 256 (6 x 6 of 128), K = 3 x 128: multi-tile, two passes of the unrolled loop
-    M, N, K = 768, 768, 384
+    # 3 x 3 tiles of 256 (6 x 6 of 128), 13 K-steps of 32: multi-tile, the LDS ring wraps twice
+    M, N, K = 768, 768, 416
     a = synth.normal_bf16(31, (M, K))
     b = synth.normal_bf16(32, (K, N), 0.02)
     A, Bm = store(a, b, layout)
@@ -96,21 +96,25 @@ def test_every_tile_variant_against_oracle(oracle_mod, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_shortest_k_and_single_tile(oracle_mod, layout):
-    # K = 128 is the shortest the tile kernels take: prologue and drain only, no steady-state loop
-    M, N, K = 256, 256, 128
-    a = synth.normal_bf16(41, (M, K))
-    b = synth.normal_bf16(42, (K, N))
-    A, Bm = store(a, b, layout)
-    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    # the shortest K each tile kernel takes (its prologue fills the whole LDS ring, the main loop
+    # never runs), and one step more
+    M = N = 256
     for v in tile_variants():
-        got = run_gpu("bwd_data", M, N, K, layout, A, Bm, variant=v)
-        U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+        kmin = next(k for k in range(32, 1024, 32) if B.variant_supports(v, M, N, k, layout))
+        assert not B.variant_supports(v, M, N, kmin - 32, layout)
+        for K in (kmin, kmin + 32):
+            a = synth.normal_bf16(41 + K, (M, K))
+            b = synth.normal_bf16(42 + K, (K, N))
+            A, Bm = store(a, b, layout)
+            ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+            got = run_gpu("bwd_data", M, N, K, layout, A, Bm, variant=v)
+            U.assert_close(got, ref, f"{B.variant_name(v)} {layout} K={K}")
 
 
 # ------------------------------------------------------------------ exact integers: bit for bit
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_integer_inputs_are_bit_exact(oracle_mod, layout):
-    M, N, K = 512, 768, 640   # rectangular, 2 x 3 tiles of 256, K = 5 x 128
+    M, N, K = 512, 768, 608   # rectangular, 2 x 3 tiles of 256, 19 K-steps
     a = synth.integer_bf16(51, (M, K), -4, 4)
     b = synth.integer_bf16(52, (K, N), -4, 4)
     A, Bm = store(a, b, layout)
