@@ -87,21 +87,24 @@ struct Variant {
     tile_kernel_t fn[3];             // per layout
 };
 
-#define AXONN_TILE_VARIANT(BM, BN)                                                           \
-    {                                                                                        \
-        "mfma_" #BM "x" #BN, BM, BN, TileCfg<BM, BN>::NT, TileCfg<BM, BN>::LDS_BYTES,        \
-            TileCfg<BM, BN>::MIN_K, {                                                        \
-            gemm_tile_kernel<BM, BN, true, false>, gemm_tile_kernel<BM, BN, true, true>,     \
-                gemm_tile_kernel<BM, BN, false, false>                                       \
-        }                                                                                    \
+#define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN)                                                     \
+    {                                                                                                \
+        NAME, BM, BN, TileCfg<BM, BN, WM, WN>::NT, TileCfg<BM, BN, WM, WN>::LDS_BYTES,               \
+            TileCfg<BM, BN, WM, WN>::MIN_K, {                                                        \
+            gemm_tile_kernel<BM, BN, WM, WN, true, false>, gemm_tile_kernel<BM, BN, WM, WN, true, true>, \
+                gemm_tile_kernel<BM, BN, WM, WN, false, false>                                       \
+        }                                                                                            \
     }
 
 static const Variant g_variants[] = {
     {"naive", 0, 0, 256, 0, 0, {nullptr, nullptr, nullptr}},
-    AXONN_TILE_VARIANT(256, 256),
-    AXONN_TILE_VARIANT(256, 128),
-    AXONN_TILE_VARIANT(128, 256),
-    AXONN_TILE_VARIANT(128, 128),
+    AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2),
+    AXONN_TILE_VARIANT("mfma_256x128", 256, 128, 2, 2),
+    AXONN_TILE_VARIANT("mfma_128x256", 128, 256, 2, 2),
+    AXONN_TILE_VARIANT("mfma_128x128", 128, 128, 2, 2),
+    AXONN_TILE_VARIANT("mfma_256x256_w8", 256, 256, 2, 4),
+    AXONN_TILE_VARIANT("mfma_256x128_w8", 256, 128, 2, 4),
+    AXONN_TILE_VARIANT("mfma_128x256_w8", 128, 256, 2, 4),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -123,16 +126,16 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // K-contiguous operands are the dearer ones to stage (64-byte row segments per load), which is
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout) {
-    static const double eff[3][5] = {
-        /* variant:   naive 256x256 256x128 128x256 128x128 */
-        /* NN */ {0.0, 1.00, 0.78, 0.90, 0.72},
-        /* NT */ {0.0, 1.00, 0.74, 0.75, 0.68},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.75},
+    static const double eff[3][8] = {
+        /* variant:   naive 256x256 256x128 128x256 128x128, then the 8-wave 256x256 256x128 128x256 */
+        /* NN */ {0.0, 1.00, 0.78, 0.90, 0.72, 1.06, 0.80, 0.93},
+        /* NT */ {0.0, 1.00, 0.74, 0.75, 0.68, 0.99, 0.76, 0.74},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.75, 1.05, 0.92, 0.96},
     };
     int best = 0;
     double best_t = 0;
     for (int v = 1; v < kNumVariants; ++v) {
-        if (!variant_supports(v, M, N, K, layout)) continue;
+        if (!variant_supports(v, M, N, K, layout) || eff[layout][v] <= 0.0) continue;
         const Variant& var = g_variants[v];
         const int64_t tiles = (M / var.bm) * (N / var.bn);
         // Every CU works through ceil(tiles / 256) tiles (two small tiles resident on one CU run

@@ -89,15 +89,22 @@ __device__ __forceinline__ void direct_load16(uint32_t lds_dst, const uint8_t* b
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(base), "s"(lds_dst) : "memory", "m0");
 }
+// LDS reads.  The destination is declared read-write ("+v") on purpose: a fragment then keeps ONE
+// set of registers for the whole kernel instead of being renamed onto whatever register just went
+// dead.  That matters because an LDS read completes asynchronously and nothing in hardware orders
+// it against an MFMA that was issued earlier but is still queued in front of the matrix pipe and
+// has not read its operands yet: if the read's destination were the register such an MFMA is about
+// to read (the compiler likes to reuse a register right after its last use), the MFMA could see the
+// new value.  With fixed registers a fragment is only rewritten half a K-step after its last reader.
 template <int IMM>
 __device__ __forceinline__ void lds_read128(u32x4& dst, uint32_t addr) {
     static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset is 16 bits");
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(IMM));
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(dst) : "v"(addr), "n"(IMM));
 }
 template <int IMM>
 __device__ __forceinline__ void lds_read64_tr(u32x2& dst, uint32_t addr) {
     static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset is 16 bits");
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(IMM));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(dst) : "v"(addr), "n"(IMM));
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -105,23 +112,43 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// MFMA operand fragment of one 32-row block: eight bf16 per lane.  A b128 read fills it in one go,
+// a pair of transposing b64 reads fills its halves.
+struct Frag128 {
+    u32x4 v;
+    __device__ __forceinline__ void clear() { v = u32x4{0, 0, 0, 0}; }
+    __device__ __forceinline__ bf16x8 get() const { return __builtin_bit_cast(bf16x8, v); }
+};
+struct Frag64x2 {
+    u32x2 lo, hi;
+    __device__ __forceinline__ void clear() { lo = hi = u32x2{0, 0}; }
+    __device__ __forceinline__ bf16x8 get() const {
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
+    }
+};
 // All LDS reads issued so far have landed.  The fragment registers are made to depend on the wait
 // so that no MFMA reading them can be scheduled above it.
-template <int MI, int NI>
-__device__ __forceinline__ void wait_lds_reads(u32x4* fa, u32x4* fb) {
-    static_assert((MI == 2 || MI == 4) && (NI == 2 || NI == 4), "wave tiles are 2 or 4 blocks a side");
-    if constexpr (MI == 4 && NI == 4)
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]),
-                       "+v"(fb[3])::"memory");
-    else if constexpr (MI == 4 && NI == 2)
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1])::"memory");
-    else if constexpr (MI == 2 && NI == 4)
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3])::"memory");
+template <int N>
+__device__ __forceinline__ void tie_to_lds_wait(Frag128* f) {
+    static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 blocks a side");
+    if constexpr (N == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].v), "+v"(f[1].v), "+v"(f[2].v), "+v"(f[3].v)::"memory");
+    else if constexpr (N == 2)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].v), "+v"(f[1].v)::"memory");
     else
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1])::"memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].v)::"memory");
+}
+template <int N>
+__device__ __forceinline__ void tie_to_lds_wait(Frag64x2* f) {
+    static_assert(N == 1 || N == 2 || N == 4, "1, 2 or 4 blocks a side");
+    if constexpr (N == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi),
+                       "+v"(f[3].lo), "+v"(f[3].hi)::"memory");
+    else if constexpr (N == 2)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi)::"memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi)::"memory");
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -134,10 +161,11 @@ __device__ __forceinline__ void wait_lds_reads(u32x4* fa, u32x4* fb) {
 //   read<I, S>(frag, cursor)   fragment of 32-row block I, k16 substep S (0/1)
 // The stage offset is the only run-time part of an LDS address; everything else is an immediate.
 // ------------------------------------------------------------------------------------------------
-template <int ROWS, int REGION>
+template <int ROWS, int REGION, int NW, int NB_>
 struct OperandKContig {   // global P[row * ld + k]
-    static constexpr int QL = ROWS / 16 / 4;   // a load covers 16 rows x 64 B
-    static constexpr int NB = ROWS / 2 / 32;   // 32-row blocks per wave tile
+    static constexpr int QL = ROWS / 16 / NW;  // a load covers 16 rows x 64 B
+    static constexpr int NB = NB_;             // 32-row blocks per wave tile
+    static_assert(QL >= 1, "at least one load per wave and stage");
     struct Cursor {
         uint32_t a[2];   // [substep]
     };
@@ -171,18 +199,20 @@ struct OperandKContig {   // global P[row * ld + k]
     __device__ __forceinline__ Cursor cursor(uint32_t stage_off) const {
         return Cursor{{raddr[0] + stage_off, raddr[1] + stage_off}};
     }
+    using Frag = Frag128;
     template <int I, int S>
-    __device__ __forceinline__ void read(u32x4& f, const Cursor& c) const {
-        lds_read128<I * 2048>(f, c.a[S]);
+    __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
+        lds_read128<I * 2048>(f.v, c.a[S]);
     }
 };
 
-template <int ROWS, int REGION>
+template <int ROWS, int REGION, int NW, int NB_>
 struct OperandMNContig {   // global P[k * ld + row]
     static constexpr int ROWB = ROWS * 2;              // bytes per k-row in LDS
     static constexpr int KR = 1024 / ROWB;             // k-rows per load: 2 (256 rows) or 4 (128 rows)
-    static constexpr int QL = KB / KR / 4;
-    static constexpr int NB = ROWS / 2 / 32;
+    static constexpr int QL = KB / KR / NW;
+    static constexpr int NB = NB_;
+    static_assert(QL >= 1 && (KR == 4 || QL % 2 == 0), "loads per wave: whole, and even when a load holds two k-rows");
     static constexpr int CPR = ROWB / 16;              // 16-byte chunks per k-row
     static_assert(ROWS == 128 || ROWS == 256, "tile extents are 128 or 256");
     struct Cursor {
@@ -234,25 +264,23 @@ struct OperandMNContig {   // global P[k * ld + row]
         for (int i = 0; i < NB; ++i) c.a[i] = raddr[i] + stage_off;
         return c;
     }
+    using Frag = Frag64x2;
     template <int I, int S>
-    __device__ __forceinline__ void read(u32x4& f, const Cursor& c) const {
-        u32x2 lo, hi;   // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
-        lds_read64_tr<(16 * S) * ROWB>(lo, c.a[I]);
-        lds_read64_tr<(16 * S + 4) * ROWB>(hi, c.a[I]);
-        f[0] = lo[0];
-        f[1] = lo[1];
-        f[2] = hi[0];
-        f[3] = hi[1];
+    __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
+        // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
+        lds_read64_tr<(16 * S) * ROWB>(f.lo, c.a[I]);
+        lds_read64_tr<(16 * S + 4) * ROWB>(f.hi, c.a[I]);
     }
 };
 
 // ------------------------------------------------------------------------------------------------
 // NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile stays at 64 KB so
-// that two workgroups share a CU).
-template <int BM, int BN>
+// that two workgroups share a CU).  WM x WN waves: 2 x 2 (one wave per SIMD) or 2 x 4 (two).
+template <int BM, int BN, int WM, int WN>
 struct TileCfg {
-    static constexpr int NT = 256;
-    static constexpr int TM = BM / 2, TN = BN / 2;          // wave tile
+    static constexpr int NW = WM * WN;
+    static constexpr int NT = 64 * NW;
+    static constexpr int TM = BM / WM, TN = BN / WN;        // wave tile
     static constexpr int MI = TM / 32, NI = TN / 32;        // 32x32 blocks per wave tile
     static constexpr int STAGE_BYTES = (BM + BN) * KB * 2;  // A panel then B panel
     static constexpr int NS = (BM + BN == 512) ? 5 : (BM + BN == 384) ? 6 : 4;
@@ -261,19 +289,22 @@ struct TileCfg {
     static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
     static constexpr int MIN_K = KB * (NS - 1);             // the prologue fills NS-1 stages
     static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256), "tile extents are 128 or 256");
+    static_assert(WM == 2 && (WN == 2 || WN == 4), "4 or 8 waves");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
 // Requires M % BM == 0, N % BN == 0, K % 32 == 0, K >= TileCfg::MIN_K (checked on the host).
-template <int BM, int BN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int M, int N, int K, int tiles_m, int tiles_n, int group_m) {
-    using Cfg = TileCfg<BM, BN>;
+    using Cfg = TileCfg<BM, BN, WM, WN>;
+    constexpr int NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS;
     constexpr uint32_t SB = Cfg::STAGE_BYTES, RING = Cfg::RING_BYTES;
-    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0>, OperandMNContig<BM, 0>>::type;
-    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2>, OperandMNContig<BN, BM * KB * 2>>::type;
+    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, NW, MI>, OperandMNContig<BM, 0, NW, MI>>::type;
+    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, NW, NI>,
+                                          OperandMNContig<BN, BM * KB * 2, NW, NI>>::type;
     constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
     constexpr int NM = MI * NI;                                // MFMAs per half K-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -281,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     // ---- workgroup -> output tile: XCD-contiguous, then grouped along m ------------------------
     int pid = blockIdx.x;
@@ -310,15 +341,24 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 fa[2][MI], fb[2][NI];   // fragment double buffer: [k16 substep parity][block]
+    // fragment double buffer: [k16 substep parity][block]; cleared once because the LDS reads take
+    // them as read-write operands
+    typename OpA::Frag fa[2][MI];
+    typename OpB::Frag fb[2][NI];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[u][i].clear();
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[u][j].clear();
+    }
 
     // Nothing may be scheduled across this point (keeps the hand-made instruction order).
 #define AXONN_FENCE() __builtin_amdgcn_sched_barrier(0)
     // MFMA number IDX (i-major) of a half K-step, on fragment buffer BUF.
     auto mfma = [&](auto buf_c, auto idx_c) {
         constexpr int BUF = decltype(buf_c)::value, I = decltype(idx_c)::value / NI, J = decltype(idx_c)::value % NI;
-        acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[BUF][J]),
-                                                            __builtin_bit_cast(bf16x8, fa[BUF][I]), acc[I][J], 0, 0, 0);
+        acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[BUF][J].get(), fa[BUF][I].get(), acc[I][J], 0, 0, 0);
     };
     auto mfma_range = [&](auto buf_c, auto lo_c, auto hi_c) {
         constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
@@ -326,29 +366,35 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
     };
     auto wait_fragments = [&](auto buf_c) {
         constexpr int BUF = decltype(buf_c)::value;
-        wait_lds_reads<MI, NI>(fa[BUF], fb[BUF]);
+        tie_to_lds_wait<MI>(fa[BUF]);
+        tie_to_lds_wait<NI>(fb[BUF]);
     };
-    // Half HALF (0/1) of the fragment reads of substep S through the given cursors into buffer BUF.
+    // Cluster HALF (0/1) of the fragment reads of substep S through the given cursors into buffer BUF.
+    // The MFMAs run i-major, so the A blocks of the first half of the wave tile have had their last
+    // reader long before the half ends: they are refilled by cluster 0.  Every B block and the
+    // last A blocks are read by the final MFMAs of a half; they are refilled by cluster 1 of the
+    // following half, i.e. at least NM/2 + 1 MFMAs after their last reader was issued.
     auto read_cluster = [&](auto half_c, auto s_c, auto buf_c, const typename OpA::Cursor& ca,
                             const typename OpB::Cursor& cb) {
         constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, BUF = decltype(buf_c)::value;
-        static_for<MI / 2>([&](auto d) {
+        static_assert(MI >= 2, "cluster 0 needs an A block of its own");
+        static_for<H == 0 ? MI / 2 : MI - MI / 2>([&](auto d) {
             constexpr int I = H * (MI / 2) + decltype(d)::value;
             opa.template read<I, S>(fa[BUF][I], ca);
         });
-        static_for<NI / 2>([&](auto d) {
-            constexpr int J = H * (NI / 2) + decltype(d)::value;
-            opb.template read<J, S>(fb[BUF][J], cb);
-        });
+        if constexpr (H == 1)
+            static_for<NI>([&](auto d) { opb.template read<decltype(d)::value, S>(fb[BUF][decltype(d)::value], cb); });
     };
     // Half HALF of one operand's direct loads into the stage at stage_off.
     auto load_cluster_a = [&](auto half_c, uint32_t stage_off) {
         constexpr int H = decltype(half_c)::value;
-        static_for<QA / 2>([&](auto d) { opa.template issue<H * (QA / 2) + decltype(d)::value>(stage_off); });
+        static_for<H == 0 ? (QA + 1) / 2 : QA / 2>(
+            [&](auto d) { opa.template issue<H * ((QA + 1) / 2) + decltype(d)::value>(stage_off); });
     };
     auto load_cluster_b = [&](auto half_c, uint32_t stage_off) {
         constexpr int H = decltype(half_c)::value;
-        static_for<QB / 2>([&](auto d) { opb.template issue<H * (QB / 2) + decltype(d)::value>(stage_off); });
+        static_for<H == 0 ? (QB + 1) / 2 : QB / 2>(
+            [&](auto d) { opb.template issue<H * ((QB + 1) / 2) + decltype(d)::value>(stage_off); });
     };
     auto next_stage = [&](uint32_t off) -> uint32_t { return off + SB == RING ? 0u : off + SB; };
 
@@ -371,31 +417,34 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
     // a step and become the current ones when the step ends
     typename OpA::Cursor ca = opa.cursor(st_cur);
     typename OpB::Cursor cb = opb.cursor(st_cur);
-    read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
-    read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
 
     // ---- one K-step on the stage at st_cur ---------------------------------------------------
     //   LOAD: also fetch K-step t+NS-1 into the stage at st_load (the one step t-1 used).
     //   NEXT: a following K-step exists.
     //   VM:   direct loads that may still be in flight at the barrier (everything older has
     //         landed, in particular the whole of K-step t+1).
-    auto step = [&](auto load_c, auto next_c, auto vm_c) {
+    //   PHASE: where the two clusters of a half sit among its NM MFMAs.  With two waves per SIMD the
+    //         second wave of each SIMD (waves 4..7) uses phase 1, so that one wave's clusters fall
+    //         into the other's runs of MFMAs and the matrix pipe always has work queued.
+    auto step = [&](auto phase_c, auto load_c, auto next_c, auto vm_c) {
         constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value;
         constexpr int VM = decltype(vm_c)::value;
+        constexpr int P0 = decltype(phase_c)::value == 0 ? 1 : NM / 4 + 1;        // MFMAs before cluster 0
+        constexpr int P1 = decltype(phase_c)::value == 0 ? NM / 2 + 1 : NM / 4 + NM / 2 + 1;   // ... cluster 1
         // first half: MFMAs of substep 0 (buffer 0); substep-1 fragments into buffer 1
         wait_fragments(Int<0>{});
         AXONN_FENCE();
-        mfma(Int<0>{}, Int<0>{});
+        mfma_range(Int<0>{}, Int<0>{}, Int<P0>{});
         AXONN_FENCE();
         read_cluster(Int<0>{}, Int<1>{}, Int<1>{}, ca, cb);
         if constexpr (LOAD) load_cluster_a(Int<0>{}, st_load);
         AXONN_FENCE();
-        mfma_range(Int<0>{}, Int<1>{}, Int<NM / 2 + 1>{});
+        mfma_range(Int<0>{}, Int<P0>{}, Int<P1>{});
         AXONN_FENCE();
         read_cluster(Int<1>{}, Int<1>{}, Int<1>{}, ca, cb);
         if constexpr (LOAD) load_cluster_a(Int<1>{}, st_load);
         AXONN_FENCE();
-        mfma_range(Int<0>{}, Int<NM / 2 + 1>{}, Int<NM>{});
+        mfma_range(Int<0>{}, Int<P1>{}, Int<NM>{});
         AXONN_FENCE();
         // middle: the last fragments of this stage are in registers and K-step t+1 has landed
         wait_fragments(Int<1>{});
@@ -405,7 +454,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
         }
         AXONN_FENCE();
         // second half: MFMAs of substep 1 (buffer 1); first fragments of K-step t+1 into buffer 0
-        mfma(Int<1>{}, Int<0>{});
+        mfma_range(Int<1>{}, Int<0>{}, Int<P0>{});
         AXONN_FENCE();
         if constexpr (NEXT) {
             ca = opa.cursor(st_next);
@@ -414,7 +463,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
         }
         if constexpr (LOAD) load_cluster_b(Int<0>{}, st_load);
         AXONN_FENCE();
-        mfma_range(Int<1>{}, Int<1>{}, Int<NM / 2 + 1>{});
+        mfma_range(Int<1>{}, Int<P0>{}, Int<P1>{});
         AXONN_FENCE();
         if constexpr (NEXT) read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
         if constexpr (LOAD) {
@@ -423,7 +472,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
             opb.advance();
         }
         AXONN_FENCE();
-        mfma_range(Int<1>{}, Int<NM / 2 + 1>{}, Int<NM>{});
+        mfma_range(Int<1>{}, Int<P1>{}, Int<NM>{});
         AXONN_FENCE();
         st_load = st_cur;   // the stage just finished is the next one to refill
         st_cur = st_next;
@@ -433,11 +482,25 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(
     using No = std::false_type;
 
     const int KT = K / KB;   // at least NS - 1
-    // steady state: in flight at the barrier are K-steps t+2 .. t+NS-2 and the A part of t+NS-1
-    for (int kt = 0; kt + (NS - 1) < KT; ++kt) step(Yes{}, Yes{}, Int<(NS - 3) * NL + QA>{});
-    // drain: nothing left to fetch; K-steps t+2 .. KT-1 may still be in flight at the barrier
-    static_for<NS - 2>([&](auto j) { step(No{}, Yes{}, Int<(NS - 3 - decltype(j)::value) * NL>{}); });
-    step(No{}, No{}, Int<0>{});
+    auto main_loop = [&](auto phase_c) {
+        // The first fragments are fetched here, inside the phase's own code path: an LDS read is
+        // asynchronous and the compiler does not know it, so between a read and the wait that
+        // covers it there must be no point (such as a branch join) where it could copy the
+        // destination registers.
+        read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
+        read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
+        // steady state: in flight at the barrier are K-steps t+2 .. t+NS-2 and the A part of t+NS-1
+        for (int kt = 0; kt + (NS - 1) < KT; ++kt) step(phase_c, Yes{}, Yes{}, Int<(NS - 3) * NL + QA>{});
+        // drain: nothing left to fetch; K-steps t+2 .. KT-1 may still be in flight at the barrier
+        static_for<NS - 2>([&](auto j) { step(phase_c, No{}, Yes{}, Int<(NS - 3 - decltype(j)::value) * NL>{}); });
+        step(phase_c, No{}, No{}, Int<0>{});
+    };
+    if constexpr (NW == 8) {
+        if (wave >= 4) main_loop(Int<1>{});   // wave-uniform; both paths hit the same barriers
+        else main_loop(Int<0>{});
+    } else {
+        main_loop(Int<0>{});
+    }
     __syncthreads();   // every wave is done with the ring before the epilogue reuses LDS
 
     // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
