@@ -34,8 +34,16 @@
  * Common rules for the three entry points
  *   pointers   DEVICE pointers to bf16 (16-bit) elements, row-major, tightly
  *              packed, 16-byte aligned.  The caller owns all three buffers; the
- *              library allocates nothing, keeps no reference after return and
- *              never reads the output.  The output must not overlap an input.
+ *              library keeps no reference after return and never reads the
+ *              output.  The output must not overlap an input.
+ *   scratch    outputs of few tiles and long K are computed by split-K kernels,
+ *              which exchange fp32 partial tiles through a scratch area owned by
+ *              the library: 64 MiB of device memory per GPU, allocated (hipMalloc)
+ *              by axonn_linear_init or by the first call that needs it, and kept
+ *              until the process ends.  If it cannot be had the other kernels run.
+ *              Calls that may EXECUTE CONCURRENTLY on one GPU (different streams)
+ *              would share it: serialise them or switch split-K off
+ *              (axonn_linear_set_split_k).  Calls on one stream are always safe.
  *   stream     a hipStream_t passed as void*; NULL is the default stream.  The
  *              call enqueues work and returns; it never synchronises.
  *   fp32_accumulate
@@ -50,10 +58,12 @@
  *              shapes take a slower guarded kernel.
  *   errors     the return value is AXONN_OK (0) or a negative code below; on an
  *              error nothing has been launched.  No exceptions, no aborts.
- *   threads    re-entrant; the only process-wide state is the kernel override
- *              (axonn_linear_force_variant) used by tests and the benchmark.
- *   determinism the same inputs give the same bits on every call: no atomics,
- *              fixed summation order per kernel variant.
+ *   threads    callable from any thread; the process-wide state is the kernel
+ *              override (axonn_linear_force_variant), the split-K switch and the
+ *              scratch area described above.
+ *   determinism the same inputs give the same bits on every call: no floating-point
+ *              atomics, fixed summation order per kernel variant (split-K adds
+ *              the partial tiles in K order).
  */
 #ifndef AXONN_LINEAR_H
 #define AXONN_LINEAR_H
@@ -101,8 +111,24 @@ const char *axonn_status_string(int status);
 /* Library version, major * 10000 + minor * 100 + patch. */
 int axonn_linear_version(void);
 
+/* Optional set-up for the current device: raises the kernels' LDS limits and allocates the split-K
+ * scratch area now rather than inside the first call that needs it (do this before capturing calls
+ * into a HIP graph: an allocation is not allowed during capture).  Idempotent.  AXONN_OK, or
+ * AXONN_ERR_LAUNCH if the allocation failed (the library then works without split-K). */
+int axonn_linear_init(void);
+
+/* Allow (1, the default) or forbid (0) the automatic choice of split-K kernels, process-wide.
+ * Returns the previous setting, or AXONN_ERR_INVALID_ARG. */
+int axonn_linear_set_split_k(int enable);
+
+/* Diagnostics: how many times, on the current device, a split-K workgroup gave up waiting for a
+ * partial tile (it waits about a second; this cannot happen unless another workgroup of the same
+ * launch died).  Synchronous device-to-host copy.  *count is 0 when no split-K kernel has run. */
+int axonn_linear_split_k_timeouts(uint64_t *count);
+
 /* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any
- * shape; the others are MFMA tile kernels.  Host-only queries: no GPU is touched. */
+ * shape; the others are MFMA tile kernels ("_w8": 8 waves, "_sk2"/"_sk4": split-K over 2 or 4
+ * workgroups).  Host-only queries: no GPU is touched. */
 int axonn_linear_num_variants(void);
 /* Name such as "mfma_256x256"; NULL if `variant` is out of range. */
 const char *axonn_linear_variant_name(int variant);

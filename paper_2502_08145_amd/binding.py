@@ -24,6 +24,7 @@ EXPORTS = (
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
     "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
+    "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
 )
 
 _lib = None
@@ -67,6 +68,12 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_copy_probe.restype = ci
         L.axonn_linear_mfma_probe.argtypes = [vp, ctypes.c_size_t, ci, ci, vp, vp]
         L.axonn_linear_mfma_probe.restype = ci
+        L.axonn_linear_init.argtypes = []
+        L.axonn_linear_init.restype = ci
+        L.axonn_linear_set_split_k.argtypes = [ci]
+        L.axonn_linear_set_split_k.restype = ci
+        L.axonn_linear_split_k_timeouts.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
+        L.axonn_linear_split_k_timeouts.restype = ci
         _lib = L
     return _lib
 
@@ -100,6 +107,30 @@ def force_variant(v: int) -> None:
     rc = lib().axonn_linear_force_variant(int(v))
     if rc != AXONN_OK:
         raise AxonnError(rc, "axonn_linear_force_variant")
+
+
+def axonn_linear_init() -> None:
+    """Set up the current device (LDS limits, split-K scratch area) ahead of the first call."""
+    rc = lib().axonn_linear_init()
+    if rc != 0:
+        raise AxonnError(rc, "axonn_linear_init")
+
+
+def axonn_linear_set_split_k(enable: bool) -> bool:
+    """Allow or forbid the automatic choice of split-K kernels; returns the previous setting."""
+    rc = lib().axonn_linear_set_split_k(1 if enable else 0)
+    if rc < 0:
+        raise AxonnError(rc, "axonn_linear_set_split_k")
+    return bool(rc)
+
+
+def axonn_linear_split_k_timeouts() -> int:
+    """Number of split-K waits that were given up on the current device (0 in a healthy run)."""
+    n = ctypes.c_uint64(0)
+    rc = lib().axonn_linear_split_k_timeouts(ctypes.byref(n))
+    if rc != 0:
+        raise AxonnError(rc, "axonn_linear_split_k_timeouts")
+    return int(n.value)
 
 
 def _layout(layout) -> int:

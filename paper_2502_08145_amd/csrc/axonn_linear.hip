@@ -79,34 +79,80 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict
 // ------------------------------------------------------------------------------------------
 // Variant table
 // ------------------------------------------------------------------------------------------
-typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int);
+typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int, SplitK);
 
 struct Variant {
     const char* name;
-    int bm, bn, threads, lds_bytes, min_k;  // bm == 0: the naive kernel
+    int bm, bn, threads, lds_bytes, min_k;  // bm == 0: the naive kernel; min_k per K range
+    int splits;                      // K ranges per tile (1: no split-K)
+    int base;                        // index of the variant whose measured efficiency applies
     tile_kernel_t fn[3];             // per layout
 };
 
-#define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN)                                                     \
+#define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN, SPLITS, BASE)                                       \
     {                                                                                                \
         NAME, BM, BN, TileCfg<BM, BN, WM, WN>::NT, TileCfg<BM, BN, WM, WN>::LDS_BYTES,               \
-            TileCfg<BM, BN, WM, WN>::MIN_K, {                                                        \
-            gemm_tile_kernel<BM, BN, WM, WN, true, false>, gemm_tile_kernel<BM, BN, WM, WN, true, true>, \
-                gemm_tile_kernel<BM, BN, WM, WN, false, false>                                       \
+            TileCfg<BM, BN, WM, WN>::MIN_K, SPLITS, BASE, {                                          \
+            gemm_tile_kernel<BM, BN, WM, WN, true, false, (SPLITS > 1)>,                             \
+                gemm_tile_kernel<BM, BN, WM, WN, true, true, (SPLITS > 1)>,                          \
+                gemm_tile_kernel<BM, BN, WM, WN, false, false, (SPLITS > 1)>                         \
         }                                                                                            \
     }
 
 static const Variant g_variants[] = {
-    {"naive", 0, 0, 256, 0, 0, {nullptr, nullptr, nullptr}},
-    AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2),
-    AXONN_TILE_VARIANT("mfma_256x128", 256, 128, 2, 2),
-    AXONN_TILE_VARIANT("mfma_128x256", 128, 256, 2, 2),
-    AXONN_TILE_VARIANT("mfma_128x128", 128, 128, 2, 2),
-    AXONN_TILE_VARIANT("mfma_256x256_w8", 256, 256, 2, 4),
-    AXONN_TILE_VARIANT("mfma_256x128_w8", 256, 128, 2, 4),
-    AXONN_TILE_VARIANT("mfma_128x256_w8", 128, 256, 2, 4),
+    {"naive", 0, 0, 256, 0, 0, 1, 0, {nullptr, nullptr, nullptr}},
+    AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2, 1, 1),
+    AXONN_TILE_VARIANT("mfma_256x128", 256, 128, 2, 2, 1, 2),
+    AXONN_TILE_VARIANT("mfma_128x256", 128, 256, 2, 2, 1, 3),
+    AXONN_TILE_VARIANT("mfma_128x128", 128, 128, 2, 2, 1, 4),
+    AXONN_TILE_VARIANT("mfma_256x256_w8", 256, 256, 2, 4, 1, 5),
+    AXONN_TILE_VARIANT("mfma_256x128_w8", 256, 128, 2, 4, 1, 6),
+    AXONN_TILE_VARIANT("mfma_128x256_w8", 128, 256, 2, 4, 1, 7),
+    // split-K: 2 or 4 workgroups per 256x256 tile
+    AXONN_TILE_VARIANT("mfma_256x256_sk2", 256, 256, 2, 2, 2, 1),
+    AXONN_TILE_VARIANT("mfma_256x256_sk4", 256, 256, 2, 2, 4, 1),
+    AXONN_TILE_VARIANT("mfma_256x256_w8_sk2", 256, 256, 2, 4, 2, 5),
+    AXONN_TILE_VARIANT("mfma_256x256_w8_sk4", 256, 256, 2, 4, 4, 5),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
+
+// Split-K scratch: one area per device, allocated on first need and kept until the process ends.
+constexpr int kScratchSlots = 256;                          // slots of one 256x256 fp32 tile
+constexpr size_t kSlotBytes = 256 * 256 * sizeof(float);
+constexpr int kMaxDevices = 64;
+struct Scratch {
+    float* partials = nullptr;
+    uint32_t* flags = nullptr;      // kScratchSlots flags, then the time-out counter
+};
+static Scratch g_scratch[kMaxDevices];
+static std::mutex g_scratch_mutex;
+static std::atomic<uint32_t> g_epoch{0};
+static std::atomic<int> g_split_k_enabled{1};
+
+// The current device's scratch area, or nullptr if it cannot be had.
+static const Scratch* get_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    Scratch& sc = g_scratch[dev];
+    if (!sc.partials) {
+        void* p = nullptr;
+        const size_t flag_bytes = (kScratchSlots + 64) * sizeof(uint32_t);
+        if (hipMalloc(&p, kScratchSlots * kSlotBytes + flag_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        uint32_t* flags = reinterpret_cast<uint32_t*>(static_cast<char*>(p) + kScratchSlots * kSlotBytes);
+        if (hipMemset(flags, 0, flag_bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(p);
+            return nullptr;
+        }
+        sc.flags = flags;
+        sc.partials = static_cast<float*>(p);
+    }
+    return &sc;
+}
 
 static std::atomic<int> g_forced{-1};
 static std::once_flag g_attr_once;
@@ -116,32 +162,41 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
-    return M % var.bm == 0 && N % var.bn == 0 && K % KB == 0 && K >= var.min_k;
+    if (M % var.bm != 0 || N % var.bn != 0 || K % (KB * var.splits) != 0 || K / var.splits < var.min_k) return false;
+    return var.splits == 1 || (M / var.bm) * (N / var.bn) * (var.splits - 1) <= kScratchSlots;
 }
 
 // Tile-shape choice.  MI355X has 256 compute units; a partly filled last round of tiles costs a
-// whole tile time, and a smaller tile moves more operand bytes per flop.  Pick the variant with the smallest modelled
-// time: rounds x tile area / efficiency, where the efficiencies are throughputs measured on
-// MI355X with every CU busy (8192^3, N(0,1) data), relative to the 256x256 tile of each layout.
+// whole tile time, and a smaller tile moves more operand bytes per flop.  Pick the variant with the
+// smallest modelled time:
+//     rounds x tile area x (K per workgroup + fixed cost) / efficiency
+// where the efficiencies are throughputs measured on MI355X with every CU busy (N(0,1) data),
+// relative to the 4-wave 256x256 tile of each layout, and the fixed cost (pipeline fill, epilogue,
+// for split-K also the exchange of fp32 partial tiles) is expressed in units of k.
 // K-contiguous operands are the dearer ones to stage (64-byte row segments per load), which is
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
-static int select_variant(int64_t M, int64_t N, int64_t K, int layout) {
+// Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
+static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
     static const double eff[3][8] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, then the 8-wave 256x256 256x128 128x256 */
         /* NN */ {0.0, 1.00, 0.78, 0.90, 0.72, 1.06, 0.80, 0.93},
         /* NT */ {0.0, 1.00, 0.74, 0.75, 0.68, 0.99, 0.76, 0.74},
         /* TN */ {0.0, 1.00, 0.91, 0.90, 0.75, 1.05, 0.92, 0.96},
     };
+    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0;
     int best = 0;
     double best_t = 0;
     for (int v = 1; v < kNumVariants; ++v) {
-        if (!variant_supports(v, M, N, K, layout) || eff[layout][v] <= 0.0) continue;
         const Variant& var = g_variants[v];
-        const int64_t tiles = (M / var.bm) * (N / var.bn);
-        // Every CU works through ceil(tiles / 256) tiles (two small tiles resident on one CU run
+        if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split)) continue;
+        const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
+        // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
         // side by side at half speed each, which comes to the same).
-        const int64_t rounds = (tiles + 255) / 256;
-        const double t = (double)rounds * var.bm * var.bn / eff[layout][v];
+        const int64_t rounds = (wgs + 255) / 256;
+        if (var.splits > 1 && rounds > 1) continue;   // readers and writers of a tile run side by side
+        const double k_cost = (double)(K / var.splits) +
+                              (var.splits == 1 ? kFixedK : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
+        const double t = (double)rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
         if (best == 0 || t < best_t) {
             best = v;
             best_t = t;
@@ -182,10 +237,13 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     if (M == 0 || N == 0) return AXONN_OK;
 
     int v = g_forced.load(std::memory_order_relaxed);
+    const Scratch* scratch = nullptr;
     if (v >= 0) {
         if (!variant_supports(v, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch())) return AXONN_ERR_LAUNCH;
     } else {
-        v = select_variant(M, N, K, layout);
+        v = select_variant(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch())) v = select_variant(M, N, K, layout, false);
     }
     const Variant& var = g_variants[v];
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -208,8 +266,14 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
         const int64_t tiles = (int64_t)tiles_m * tiles_n;
         if (tiles >= ((int64_t)1 << 31)) return AXONN_ERR_UNSUPPORTED;
         const int group_m = tiles_m < 8 ? tiles_m : 8;
-        hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)tiles), dim3(var.threads), var.lds_bytes, s, A, B, C,
-                           (int)M, (int)N, (int)K, tiles_m, tiles_n, group_m);
+        SplitK sk{nullptr, nullptr, nullptr, 0u, 1};
+        if (var.splits > 1) {
+            uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
+            if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;   // flags start at 0
+            sk = SplitK{scratch->partials, scratch->flags, scratch->flags + kScratchSlots, epoch, var.splits};
+        }
+        hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)(tiles * var.splits)), dim3(var.threads), var.lds_bytes, s,
+                           A, B, C, (int)M, (int)N, (int)K, tiles_m, tiles_n, group_m, sk);
     }
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
@@ -257,7 +321,37 @@ int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, 
 
 int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
     if (M < 0 || N < 0 || K < 0 || layout < 0 || layout > 2) return AXONN_ERR_INVALID_ARG;
-    return axonn::select_variant(M, N, K, layout);
+    return axonn::select_variant(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
+}
+
+int axonn_linear_init(void) {
+    std::call_once(axonn::g_attr_once, axonn::raise_lds_limits);
+    return axonn::get_scratch() ? AXONN_OK : AXONN_ERR_LAUNCH;
+}
+
+int axonn_linear_set_split_k(int enable) {
+    if (enable != 0 && enable != 1) return AXONN_ERR_INVALID_ARG;
+    return axonn::g_split_k_enabled.exchange(enable, std::memory_order_relaxed);
+}
+
+int axonn_linear_split_k_timeouts(uint64_t* count) {
+    if (!count) return AXONN_ERR_INVALID_ARG;
+    *count = 0;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= axonn::kMaxDevices) return AXONN_ERR_LAUNCH;
+    uint32_t* counter = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
+        if (axonn::g_scratch[dev].flags) counter = axonn::g_scratch[dev].flags + axonn::kScratchSlots;
+    }
+    if (!counter) return AXONN_OK;   // no split-K kernel has run on this device
+    uint32_t v = 0;
+    if (hipMemcpy(&v, counter, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return AXONN_ERR_LAUNCH;
+    }
+    *count = v;
+    return AXONN_OK;
 }
 
 int axonn_linear_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {

@@ -89,13 +89,12 @@ __device__ __forceinline__ void direct_load16(uint32_t lds_dst, const uint8_t* b
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(base), "s"(lds_dst) : "memory", "m0");
 }
-// LDS reads.  The destination is declared read-write ("+v") on purpose: a fragment then keeps ONE
-// set of registers for the whole kernel instead of being renamed onto whatever register just went
-// dead.  That matters because an LDS read completes asynchronously and nothing in hardware orders
-// it against an MFMA that was issued earlier but is still queued in front of the matrix pipe and
-// has not read its operands yet: if the read's destination were the register such an MFMA is about
-// to read (the compiler likes to reuse a register right after its last use), the MFMA could see the
-// new value.  With fixed registers a fragment is only rewritten half a K-step after its last reader.
+// LDS reads.  An LDS read completes asynchronously and the compiler does not know that: to it the
+// asm statement has produced its result at once.  The destination is therefore declared read-write
+// ("+v"), which pins a fragment to ONE set of registers for the whole kernel: the compiler can then
+// neither rename the destination onto a register that an MFMA issued just before still has to read,
+// nor satisfy a later use from a copy made before the data arrived.  (For the same reason the reads
+// and the s_waitcnt that covers them always sit in the same straight-line piece of code.)
 template <int IMM>
 __device__ __forceinline__ void lds_read128(u32x4& dst, uint32_t addr) {
     static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset is 16 bits");
@@ -274,6 +273,22 @@ struct OperandMNContig {   // global P[k * ld + row]
 };
 
 // ------------------------------------------------------------------------------------------------
+// Split-K: when an output has too few tiles to occupy the chip, `splits` workgroups share a tile,
+// each reducing one contiguous K range.  The workgroups of ranges 1..splits-1 ("writers") park their
+// fp32 accumulators in a scratch slot and raise a flag; the workgroup of range 0 ("reader") adds the
+// slots to its own accumulators in range order and writes C, so the result does not depend on timing.
+// Writers never wait and have the lower workgroup ids on every XCD, so they are dispatched before the
+// readers that depend on them and a reader's wait always ends; the wait is bounded anyway.
+struct SplitK {
+    float* partials;      // [(splits-1) * tiles] slots of BM*BN floats, in accumulator order
+    uint32_t* flags;      // [(splits-1) * tiles]; a slot is valid when its flag equals `epoch`
+    uint32_t* timeouts;   // incremented when a reader gives up waiting (never, unless a writer died)
+    uint32_t epoch;       // differs from launch to launch: flags need no clearing
+    int splits;           // 1: no split
+};
+constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~3 us per probe
+
+// ------------------------------------------------------------------------------------------------
 // NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile stays at 64 KB so
 // that two workgroups share a CU).  WM x WN waves: 2 x 2 (one wave per SIMD) or 2 x 4 (two).
 template <int BM, int BN, int WM, int WN>
@@ -294,10 +309,12 @@ struct TileCfg {
 };
 
 // Requires M % BM == 0, N % BN == 0, K % 32 == 0, K >= TileCfg::MIN_K (checked on the host).
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC>
+// With SPLITK the grid holds sk.splits workgroups per tile and additionally (K / sk.splits) % 32 == 0,
+// K / sk.splits >= TileCfg::MIN_K.
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
-    int M, int N, int K, int tiles_m, int tiles_n, int group_m) {
+    int M, int N, int K, int tiles_m, int tiles_n, int group_m, SplitK sk) {
     using Cfg = TileCfg<BM, BN, WM, WN>;
     constexpr int NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS;
@@ -315,9 +332,27 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- workgroup -> output tile: XCD-contiguous, then grouped along m ------------------------
+    // (the hardware hands workgroup b to XCD b % 8, in order of b on each XCD)
     int pid = blockIdx.x;
     const int nwg = gridDim.x;
-    if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+    int krange = 0, ktotal = K;   // this workgroup's K range index and length
+    if constexpr (SPLITK) {
+        const int splits = sk.splits, tiles = tiles_m * tiles_n;
+        if (nwg % (8 * splits) == 0) {
+            // XCD x owns tiles [x*tp, (x+1)*tp): first the workgroups of the last K range, ... last
+            // those of range 0
+            const int tp = (nwg >> 3) / splits, li = pid >> 3;
+            krange = splits - 1 - li / tp;
+            pid = (pid & 7) * tp + li % tp;
+        } else {
+            krange = splits - 1 - pid / tiles;
+            pid = pid % tiles;
+        }
+        ktotal = K / splits;
+    } else {
+        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+    }
+    const int tile_id = pid;
     const int group_sz = group_m * tiles_n;
     const int group = pid / group_sz;
     const int first_m = group * group_m;
@@ -330,8 +365,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     const uint32_t lds0 = lds_address(smem);
     OpA opa;
     OpB opb;
-    opa.init(A, m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM);
-    opb.init(B, n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN);
+    const int64_t k0 = (int64_t)krange * ktotal;
+    opa.init(A + (A_KC ? k0 : k0 * M), m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM);
+    opb.init(B + (B_KC ? k0 : k0 * N), n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN);
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -481,7 +517,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     using Yes = std::true_type;
     using No = std::false_type;
 
-    const int KT = K / KB;   // at least NS - 1
+    const int KT = ktotal / KB;   // at least NS - 1
     auto main_loop = [&](auto phase_c) {
         // The first fragments are fetched here, inside the phase's own code path: an LDS read is
         // asynchronous and the compiler does not know it, so between a read and the wait that
@@ -502,6 +538,64 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         main_loop(Int<0>{});
     }
     __syncthreads();   // every wave is done with the ring before the epilogue reuses LDS
+
+    // ---- split-K exchange: slot element ((wave*MI*NI + i*NI + j)*4 + g)*64 + lane, 16 bytes each ---
+    if constexpr (SPLITK) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const int tiles = tiles_m * tiles_n;
+        const size_t in_slot = (size_t)wave * (MI * NI * 4 * 64) + lane;
+        if (krange != 0) {
+            const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
+            f32x4* dst = reinterpret_cast<f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        dst[((i * NI + j) * 4 + g) * 64] = f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1],
+                                                                 acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+            // Cache maintenance is dear on a chip of eight private L2s (a device-scope release writes
+            // the L2 back, an acquire invalidates it), so each workgroup does it once: the barrier
+            // orders every thread's stores before thread 0's release, and thread 0's acquire before
+            // every thread's loads.
+            __syncthreads();
+            if (t == 0) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                __hip_atomic_store(&sk.flags[slot], sk.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            return;
+        }
+        for (int r = 1; r < sk.splits; ++r) {
+            const size_t slot = (size_t)(r - 1) * tiles + tile_id;
+            if (t == 0) {
+                uint32_t probes = 0;
+                while (__hip_atomic_load(&sk.flags[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != sk.epoch) {
+                    if (++probes > kSplitSpinLimit) {
+                        atomicAdd(sk.timeouts, 1u);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(32);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // no stale cached copy of the slot
+            }
+            __syncthreads();
+            const f32x4* src = reinterpret_cast<const f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+            // a row of blocks at a time: all its loads are in flight together
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                f32x4 v[NI * 4];
+#pragma unroll
+                for (int q = 0; q < NI * 4; ++q) v[q] = __builtin_nontemporal_load(src + (i * NI * 4 + q) * 64);
+                AXONN_FENCE();
+#pragma unroll
+                for (int q = 0; q < NI * 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][q / 4][4 * (q % 4) + e] += v[q][e];
+                AXONN_FENCE();
+            }
+        }
+    }
 
     // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
     // acc[i][j][4g + e] = C[m = i*32 + l%32][n = j*32 + 8g + 4*(l/32) + e]

@@ -83,7 +83,10 @@ def test_variant_table_and_selection():
             assert not B.variant_supports(v, 1024, 1024, 1000, lay)
             assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 32
             assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
-            assert B.variant_supports(v, 256, 256, 160, lay)
+            splits = {"sk2": 2, "sk4": 4}.get(names[v].rsplit("_", 1)[-1], 1)
+            assert B.variant_supports(v, 256, 256, 160 * splits, lay)   # per K range
+            # split-K keeps (splits - 1) partial tiles per output tile in a scratch area of 256 tiles
+            assert B.variant_supports(v, 4096, 4096, 4096, lay) == (splits <= 2)
         # ragged or degenerate shapes go to the guarded kernel, large ones to an MFMA kernel
         assert B.select_variant(100, 200, 300, lay) == 0
         assert B.select_variant(256, 256, 0, lay) == 0
@@ -91,6 +94,13 @@ def test_variant_table_and_selection():
             v = B.select_variant(*shape, lay)
             assert v > 0 and B.variant_supports(v, *shape, lay)
     assert B.select_variant(-1, 8, 8, "NN") == B.AXONN_ERR_INVALID_ARG
+    # few tiles and a long K: split-K, unless it is switched off
+    for lay in ("NN", "NT", "TN"):
+        assert "_sk" in names[B.select_variant(2048, 4096, 16384, lay)]
+        assert B.axonn_linear_set_split_k(False) is True
+        assert "_sk" not in names[B.select_variant(2048, 4096, 16384, lay)]
+        assert B.axonn_linear_set_split_k(True) is False
+        assert "_sk" not in names[B.select_variant(8192, 8192, 8192, lay)]
     with pytest.raises(B.AxonnError):
         B.force_variant(n)
     B.force_variant(-1)

@@ -46,6 +46,18 @@ def tile_variants():
     return [v for v in range(1, B.num_variants())]
 
 
+def splits_of(v):
+    """K ranges per tile of a variant (split-K variants are named ..._sk2 / ..._sk4)."""
+    return {"sk2": 2, "sk4": 4}.get(B.variant_name(v).rsplit("_", 1)[-1], 1)
+
+
+def usable(v, M, N, K, layout):
+    """Every plain tile variant must take the test shape; a split-K one may decline it."""
+    ok = B.variant_supports(v, M, N, K, layout)
+    assert ok or splits_of(v) > 1, (B.variant_name(v), M, N, K, layout)
+    return ok
+
+
 @pytest.fixture(autouse=True)
 def _announce(request):
     print(f"\n[gpu-test] {request.node.name}", flush=True)
@@ -80,18 +92,51 @@ def test_k_zero_gives_zero_and_empty_outputs_are_ok():
 # ------------------------------------------------------------------ every tile kernel, several tiles
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_every_tile_variant_against_oracle(oracle_mod, layout):
-    # 3 x 3 tiles of 256 (6 x 6 of 128), 13 K-steps of 32: multi-tile, the LDS ring wraps twice
-    M, N, K = 768, 768, 416
-    a = synth.normal_bf16(31, (M, K))
-    b = synth.normal_bf16(32, (K, N), 0.02)
+    # 3 x 3 tiles of 256 (6 x 6 of 128), 13 K-steps of 32 per workgroup: multi-tile, the LDS ring
+    # wraps twice; split-K variants get 13 steps per K range (9 tiles x splits workgroups is not a
+    # multiple of 8: the plain workgroup -> tile mapping)
+    M, N = 768, 768
+    for splits in (1, 2, 4):
+        K = 416 * splits
+        a = synth.normal_bf16(31 + splits, (M, K))
+        b = synth.normal_bf16(32 + splits, (K, N), 0.02)
+        A, Bm = store(a, b, layout)
+        ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+        ran = 0
+        for v in tile_variants():
+            if splits_of(v) != splits:
+                continue
+            assert B.variant_supports(v, M, N, K, layout)
+            got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+            nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+            # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
+            assert nw < 4e-3, (B.variant_name(v), nw)
+            ran += 1
+        assert ran >= 2
+    assert B.axonn_linear_split_k_timeouts() == 0
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_split_k_xcd_mapping_and_repeated_launches(oracle_mod, layout):
+    # 2 x 4 tiles of 256: with 2 or 4 K ranges the workgroup count is a multiple of 8 * splits, the
+    # mapping that keeps the workgroups of one tile on one XCD.  Three launches in a row reuse the
+    # same scratch slots with a new epoch each; integer data makes the comparison exact.
+    M, N, K = 512, 1024, 1792
+    a = synth.integer_bf16(91, (M, K), -4, 4)
+    b = synth.integer_bf16(92, (K, N), -4, 4)
     A, Bm = store(a, b, layout)
-    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
+    ran = 0
     for v in tile_variants():
+        if splits_of(v) == 1:
+            continue
         assert B.variant_supports(v, M, N, K, layout)
-        got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
-        nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
-        # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
-        assert nw < 4e-3, (B.variant_name(v), nw)
+        for rep in range(3):
+            got = run_gpu("bwd_data", M, N, K, layout, A, Bm, variant=v)
+            assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
+        ran += 1
+    assert ran >= 4
+    assert B.axonn_linear_split_k_timeouts() == 0
 
 
 @pytest.mark.parametrize("layout", LAYOUTS)
@@ -102,7 +147,7 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
     for v in tile_variants():
         kmin = next(k for k in range(32, 1024, 32) if B.variant_supports(v, M, N, k, layout))
         assert not B.variant_supports(v, M, N, kmin - 32, layout)
-        for K in (kmin, kmin + 32):
+        for K in (kmin, kmin + 32 * splits_of(v)):
             a = synth.normal_bf16(41 + K, (M, K))
             b = synth.normal_bf16(42 + K, (K, N))
             A, Bm = store(a, b, layout)
@@ -114,13 +159,14 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
 # ------------------------------------------------------------------ exact integers: bit for bit
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_integer_inputs_are_bit_exact(oracle_mod, layout):
-    M, N, K = 512, 768, 608   # rectangular, 2 x 3 tiles of 256, 19 K-steps
+    M, N, K = 512, 768, 640   # rectangular, 2 x 3 tiles of 256, 20 K-steps (5 per range when split in 4)
     a = synth.integer_bf16(51, (M, K), -4, 4)
     b = synth.integer_bf16(52, (K, N), -4, 4)
     A, Bm = store(a, b, layout)
     ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
     want = U.f64_to_bf16_bits_rne(ref)
     for v in [0] + tile_variants():
+        assert B.variant_supports(v, M, N, K, layout)
         got = run_gpu("bwd_weight", M, N, K, layout, A, Bm, variant=v)
         bad = np.argwhere(got != want)
         assert bad.size == 0, f"{B.variant_name(v)} {layout}: {len(bad)} mismatches, first at {bad[0]}"
@@ -142,6 +188,8 @@ def test_position_coded_operands_catch_any_index_slip(oracle_mod, layout):
     ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
     assert np.array_equal(ref, b[sel].astype(np.float64))
     for v in [0] + tile_variants():
+        if not usable(v, M, N, K, layout):
+            continue
         got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
         assert np.array_equal(U.bits_to_f64(got), ref), f"{B.variant_name(v)} {layout}"
 
