@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const uint16_t* __restr
         const uint16_t b = (LAYOUT == AXONN_NT) ? B[j * K + k] : B[k * N + j];
         acc += __builtin_bit_cast(float, (uint32_t)a << 16) * __builtin_bit_cast(float, (uint32_t)b << 16);
     }
-    C[i * N + j] = (uint16_t)f32_to_bf16_rne(acc);
+    C[i * N + j] = (uint16_t)(pack2_bf16(acc, 0.f) & 0xFFFFu);
 }
 
 // Plain copy of `n16` 16-byte words: a kernel of exactly known HBM traffic (n16 * 16 bytes read and

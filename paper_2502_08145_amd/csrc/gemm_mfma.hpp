@@ -68,14 +68,13 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs; overflow rounds to inf).
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
-    uint32_t u = __builtin_bit_cast(uint32_t, x);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// Two fp32 -> two bf16 in one word (lo in bits 0..15), round to nearest even; overflow rounds to
+// inf, NaN stays NaN.  gfx950 has an instruction for exactly this (v_cvt_pk_bf16_f32), which the
+// compiler selects for the vector conversion.
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
@@ -405,21 +404,20 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         tie_to_lds_wait<MI>(fa[BUF]);
         tie_to_lds_wait<NI>(fb[BUF]);
     };
-    // Cluster HALF (0/1) of the fragment reads of substep S through the given cursors into buffer BUF.
-    // The MFMAs run i-major, so the A blocks of the first half of the wave tile have had their last
-    // reader long before the half ends: they are refilled by cluster 0.  Every B block and the
-    // last A blocks are read by the final MFMAs of a half; they are refilled by cluster 1 of the
-    // following half, i.e. at least NM/2 + 1 MFMAs after their last reader was issued.
+    // Cluster HALF (0/1) of the fragment reads of substep S through the given cursors into buffer BUF:
+    // the MI + NI blocks (A first) are split evenly over the two clusters.  The buffer being filled
+    // was last read by MFMAs of the previous half K-step, all issued before this half began.
     auto read_cluster = [&](auto half_c, auto s_c, auto buf_c, const typename OpA::Cursor& ca,
                             const typename OpB::Cursor& cb) {
         constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, BUF = decltype(buf_c)::value;
-        static_assert(MI >= 2, "cluster 0 needs an A block of its own");
-        static_for<H == 0 ? MI / 2 : MI - MI / 2>([&](auto d) {
-            constexpr int I = H * (MI / 2) + decltype(d)::value;
-            opa.template read<I, S>(fa[BUF][I], ca);
+        constexpr int NBLK = MI + NI, FIRST = H == 0 ? 0 : NBLK / 2, LAST = H == 0 ? NBLK / 2 : NBLK;
+        static_for<LAST - FIRST>([&](auto d) {
+            constexpr int Q = FIRST + decltype(d)::value;
+            if constexpr (Q < MI)
+                opa.template read<Q, S>(fa[BUF][Q], ca);
+            else
+                opb.template read<Q - MI, S>(fb[BUF][Q - MI], cb);
         });
-        if constexpr (H == 1)
-            static_for<NI>([&](auto d) { opb.template read<decltype(d)::value, S>(fb[BUF][decltype(d)::value], cb); });
     };
     // Half HALF of one operand's direct loads into the stage at stage_off.
     auto load_cluster_a = [&](auto half_c, uint32_t stage_off) {
