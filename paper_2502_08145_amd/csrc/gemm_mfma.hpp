@@ -83,7 +83,8 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 
 // One wave-level direct load: lane l fetches 16 bytes at base + voff and they land in LDS at
 // lds_dst + 16*l (lds_dst and base wave-uniform).  M0 carries the LDS address; the s_nop covers
-// the M0-write -> LDS-DMA hazard.  Completion is tracked by vmcnt.
+// the M0-write -> LDS-DMA hazard.  Completion is tracked by vmcnt.  (No immediate offset is used:
+// the hardware would add it to the LDS address as well.)
 __device__ __forceinline__ void direct_load16(uint32_t lds_dst, const uint8_t* base, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(base), "s"(lds_dst) : "memory", "m0");
@@ -153,8 +154,10 @@ __device__ __forceinline__ void tie_to_lds_wait(Frag64x2* f) {
 // Operand policies.  ROWS = tile extent along m (or n); REGION = byte offset of the operand's
 // panel inside a stage.  Each policy gives
 //   init(...)                  per-lane / per-wave constants
-//   issue<C>(stage_off)        the C-th of QL direct loads of this wave into the stage at stage_off
+//   issue<C, AHEAD>(stage_off) the C-th of QL direct loads of this wave into the stage at stage_off,
+//                              for the K-step AHEAD (0/1) steps past the global window
 //   advance()                  move the global window one K-step on
+//   PAIR                       see below: the operand wants its loads issued two K-steps at a time
 //   cursor(stage_off)          the VGPR addresses for reading that stage (made once per K-step)
 //   read<I, S>(frag, cursor)   fragment of 32-row block I, k16 substep S (0/1)
 // The stage offset is the only run-time part of an LDS address; everything else is an immediate.
@@ -164,24 +167,47 @@ struct OperandKContig {   // global P[row * ld + k]
     static constexpr int QL = ROWS / 16 / NW;  // a load covers 16 rows x 64 B
     static constexpr int NB = NB_;             // 32-row blocks per wave tile
     static_assert(QL >= 1, "at least one load per wave and stage");
+    // A row's 32 k of one K-step are half a 128-byte cache line.  Fetching the two halves a K-step
+    // apart costs a second trip to L2 (the L1 has turned over by then); fetched back to back the
+    // second one hits in L1.  So the loads of such an operand go out in pairs: the same 16 rows for
+    // two consecutive K-steps, into two stages.  A wave's QL row groups are served alternately:
+    // the even ones in even K-steps, the odd ones in odd K-steps (needs QL even); which of the two
+    // is a run-time state (row offset folded into voff, LDS offset in lds_par), so that the K loop
+    // is one piece of code.
+    static constexpr bool PAIR = QL % 2 == 0;
+    static constexpr int NBASE = PAIR ? QL / 2 : QL;   // row groups with a base pointer of their own
     struct Cursor {
         uint32_t a[2];   // [substep]
     };
-    const uint8_t* base[QL];                   // uniform: first row of each load, k = 0
-    uint32_t voff;                             // per lane: row-in-load * ld + fetched chunk * 16
-    uint32_t lds_dst[QL];                      // uniform: destination inside stage 0
+    const uint8_t* base[NBASE];                  // uniform: first row of load c (PAIR: of load 2c), k = 0
+    uint32_t lds_dst[NBASE];                  // uniform: its destination inside stage 0
+    uint32_t voff[2];                          // per lane: row-in-load * ld + fetched chunk * 16 + window
+                                               // (+ 16 rows when the odd groups are served); [1]: one K-step on
+    uint32_t lds_par;                          // uniform, PAIR: 1024 when the odd groups are served
+    uint32_t step_add;                         // uniform, PAIR: what advance() adds to voff
     uint32_t raddr[2];                         // [substep]: read address of block 0 in stage 0
 
+    // first_step_odd: the first (virtual) K-step of the load schedule serves the odd row groups
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
-                                         uint32_t lds0, int wave_row_base) {
+                                         uint32_t lds0, int wave_row_base, bool first_step_odd) {
         const uint8_t* origin = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * ld_bytes;
+        constexpr int STRIDE = PAIR ? 2 : 1;
 #pragma unroll
-        for (int c = 0; c < QL; ++c) {
-            base[c] = origin + (size_t)(16 * (wave * QL + c)) * ld_bytes;
-            lds_dst[c] = lds0 + REGION + (wave * QL + c) * 1024;
+        for (int c = 0; c < NBASE; ++c) {
+            base[c] = origin + (size_t)(16 * (wave * QL + STRIDE * c)) * ld_bytes;
+            lds_dst[c] = lds0 + REGION + (wave * QL + STRIDE * c) * 1024;
         }
         // lane -> LDS slot (row = lane>>2, slot = lane&3); that slot holds chunk slot ^ ((row>>2)&3)
-        voff = (lane >> 2) * ld_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        voff[0] = (lane >> 2) * ld_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        const uint32_t group_bytes = 16 * ld_bytes;
+        lds_par = 0;
+        step_add = KB * 2 + group_bytes;
+        if (PAIR && first_step_odd) {
+            voff[0] += group_bytes;
+            lds_par = 1024;
+            step_add = KB * 2 - group_bytes;
+        }
+        voff[1] = voff[0] + KB * 2;
         // reader: row = wave_row_base + 32*I + lane%32 ((row>>2)&3 does not depend on I),
         // chunk = 2*S + lane/32
         const uint32_t row = wave_row_base + (lane & 31);
@@ -189,11 +215,35 @@ struct OperandKContig {   // global P[row * ld + k]
         raddr[0] = a0;
         raddr[1] = a0 ^ 32;
     }
-    template <int C>
+    // Load number C of the current K-step (PAIR: for pair C of the row groups now served), for the
+    // K-step AHEAD past the window, into the stage at stage_off.
+    template <int C, int AHEAD>
     __device__ __forceinline__ void issue(uint32_t stage_off) const {
-        direct_load16(lds_dst[C] + stage_off, base[C], voff);
+        static_assert(C < NBASE && (AHEAD == 0 || PAIR), "no such load");
+        if constexpr (PAIR)
+            direct_load16(__builtin_amdgcn_readfirstlane(lds_dst[C] + stage_off + lds_par), base[C], voff[AHEAD]);
+        else
+            direct_load16(lds_dst[C] + stage_off, base[C], voff[0]);
     }
-    __device__ __forceinline__ void advance() { voff += KB * 2; }
+    // next K-step: window one step on and, PAIR, the other row groups
+    __device__ __forceinline__ void advance() {
+        if constexpr (PAIR) {
+            voff[0] += step_add;
+            voff[1] += step_add;
+            step_add = 4 * KB - step_add;
+            lds_par ^= 1024;
+        } else {
+            voff[0] += KB * 2;
+        }
+    }
+    // PAIR: the other row groups, same window
+    __device__ __forceinline__ void flip() {
+        static_assert(PAIR, "paired operands only");
+        voff[0] += step_add - KB * 2;
+        voff[1] += step_add - KB * 2;
+        step_add = 4 * KB - step_add;
+        lds_par ^= 1024;
+    }
     __device__ __forceinline__ Cursor cursor(uint32_t stage_off) const {
         return Cursor{{raddr[0] + stage_off, raddr[1] + stage_off}};
     }
@@ -223,7 +273,7 @@ struct OperandMNContig {   // global P[k * ld + row]
     uint32_t raddr[NB];        // [block]: read address in stage 0 for substep 0, first four k
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
-                                         uint32_t lds0, int wave_row_base) {
+                                         uint32_t lds0, int wave_row_base, bool /*first_step_odd*/) {
         const uint8_t* origin = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * 2;
 #pragma unroll
         for (int c = 0; c < QL; ++c) {
@@ -248,8 +298,11 @@ struct OperandMNContig {   // global P[k * ld + row]
             raddr[i] = lds0 + REGION + (kq + 8 * (g >> 1)) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
         }
     }
-    template <int C>
+    static constexpr bool PAIR = false;   // a load already covers whole cache lines
+    static constexpr int NBASE = QL;
+    template <int C, int AHEAD>
     __device__ __forceinline__ void issue(uint32_t stage_off) const {
+        static_assert(AHEAD == 0, "loaded one K-step at a time");
         direct_load16(lds_dst[C] + stage_off, base[C], voff[C & 1]);
     }
     __device__ __forceinline__ void advance() {
@@ -288,8 +341,8 @@ struct SplitK {
 constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~3 us per probe
 
 // ------------------------------------------------------------------------------------------------
-// NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile stays at 64 KB so
-// that two workgroups share a CU).  WM x WN waves: 2 x 2 (one wave per SIMD) or 2 x 4 (two).
+// NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile takes 80 KB so that
+// two workgroups share a CU).  WM x WN waves: 2 x 2 (one wave per SIMD) or 2 x 4 (two).
 template <int BM, int BN, int WM, int WN>
 struct TileCfg {
     static constexpr int NW = WM * WN;
@@ -297,7 +350,7 @@ struct TileCfg {
     static constexpr int TM = BM / WM, TN = BN / WN;        // wave tile
     static constexpr int MI = TM / 32, NI = TN / 32;        // 32x32 blocks per wave tile
     static constexpr int STAGE_BYTES = (BM + BN) * KB * 2;  // A panel then B panel
-    static constexpr int NS = (BM + BN == 512) ? 5 : (BM + BN == 384) ? 6 : 4;
+    static constexpr int NS = (BM + BN == 512) ? 5 : (BM + BN == 384) ? 6 : 5;
     static constexpr int RING_BYTES = NS * STAGE_BYTES;
     static constexpr int EPI_BYTES = BM * BN * 2;
     static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
@@ -305,6 +358,29 @@ struct TileCfg {
     static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256), "tile extents are 128 or 256");
     static_assert(WM == 2 && (WN == 2 || WN == 4), "4 or 8 waves");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
+};
+
+// Book-keeping of the direct loads in flight (vmcnt counts them in issue order).  A K-step is of
+// kind 2 (issues all NL loads of a wave), 1 (only the first halves of paired operands' pairs) or 0
+// (none); the steps after the last full one are "tail" steps 0, 1, ...; steps before it (negative
+// index) are full.  At the barrier in the middle of a step the loads of the last NS-LAG steps and
+// of the step's own first half (operand A) may still be in flight.
+template <int QA, int QB, bool PAIR_A, bool PAIR_B, int NS>
+struct LoadPlan {
+    static constexpr int NL = QA + QB;
+    static constexpr bool ANY_PAIR = PAIR_A || PAIR_B;
+    static constexpr int LAG = ANY_PAIR ? 4 : 3;
+    static_assert(NS >= LAG, "ring too short");
+    static constexpr int issued(int kind) {
+        return kind == 2 ? NL : kind == 1 ? (PAIR_A ? QA / 2 : 0) + (PAIR_B ? QB / 2 : 0) : 0;
+    }
+    static constexpr int issued_first_half(int kind) { return kind == 2 ? QA : kind == 1 ? (PAIR_A ? QA / 2 : 0) : 0; }
+    static constexpr int tail_kind(int j) { return j < 0 ? 2 : (ANY_PAIR && j == 0) ? 1 : 0; }
+    static constexpr int tail_vm(int j) {
+        int n = issued_first_half(tail_kind(j));
+        for (int s = j - (NS - LAG); s < j; ++s) n += issued(tail_kind(s));
+        return n;
+    }
 };
 
 // Requires M % BM == 0, N % BN == 0, K % 32 == 0, K >= TileCfg::MIN_K (checked on the host).
@@ -365,8 +441,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     OpA opa;
     OpB opb;
     const int64_t k0 = (int64_t)krange * ktotal;
-    opa.init(A + (A_KC ? k0 : k0 * M), m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM);
-    opb.init(B + (B_KC ? k0 : k0 * N), n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN);
+    // the load schedule starts NS-1 K-steps before K-step 0 (see "direct loads" below)
+    constexpr bool FIRST_ODD = (NS - 1) % 2 == 1;
+    opa.init(A + (A_KC ? k0 : k0 * M), m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM, FIRST_ODD);
+    opb.init(B + (B_KC ? k0 : k0 * N), n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN, FIRST_ODD);
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -419,50 +497,78 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
                 opb.template read<Q - MI, S>(fb[BUF][Q - MI], cb);
         });
     };
-    // Half HALF of one operand's direct loads into the stage at stage_off.
-    auto load_cluster_a = [&](auto half_c, uint32_t stage_off) {
-        constexpr int H = decltype(half_c)::value;
-        static_for<H == 0 ? (QA + 1) / 2 : QA / 2>(
-            [&](auto d) { opa.template issue<H * ((QA + 1) / 2) + decltype(d)::value>(stage_off); });
+    // ---- direct loads -----------------------------------------------------------------------
+    // During K-step t a wave fetches, per operand, QL loads:
+    //   plain operand   all its loads of K-step t+NS-1, into the stage K-step t-1 used (stage "far");
+    //   paired operand  half its row groups (even ones if t is even, else the odd ones) for the TWO
+    //                   K-steps t+NS-2 and t+NS-1, back to back, into the stages "near" (the one
+    //                   K-step t-2 used) and "far".
+    // Either way a stage is refilled only after the barrier that ended its last use, every K-step
+    // issues the same NL loads, and K-step u is complete once the loads of step u-NS+1 (plain) or
+    // u-NS+2 (any operand paired) are.  KIND: 2 = all of the above, 1 = K-step t+NS-1 no longer
+    // exists (a paired operand still fetches its half of t+NS-2), 0 = nothing.
+    constexpr bool ANY_PAIR = OpA::PAIR || OpB::PAIR;
+    auto issue_loads = [&](auto op_c, auto kind_c, auto half_c, uint32_t st_near, uint32_t st_far) {
+        constexpr bool IS_A = decltype(op_c)::value == 0;
+        constexpr int KIND = decltype(kind_c)::value, H = decltype(half_c)::value;
+        using Op = typename std::conditional<IS_A, OpA, OpB>::type;
+        auto& op = [&]() -> auto& { if constexpr (IS_A) return opa; else return opb; }();
+        constexpr int NB = Op::NBASE, FIRST = H == 0 ? 0 : (NB + 1) / 2, LAST = H == 0 ? (NB + 1) / 2 : NB;
+        static_for<LAST - FIRST>([&](auto d) {
+            constexpr int C = FIRST + decltype(d)::value;
+            if constexpr (Op::PAIR) {
+                if constexpr (KIND >= 1) op.template issue<C, 0>(st_near);
+                if constexpr (KIND == 2) op.template issue<C, 1>(st_far);
+            } else {
+                if constexpr (KIND == 2) op.template issue<C, 0>(st_far);
+            }
+        });
     };
-    auto load_cluster_b = [&](auto half_c, uint32_t stage_off) {
-        constexpr int H = decltype(half_c)::value;
-        static_for<H == 0 ? (QB + 1) / 2 : QB / 2>(
-            [&](auto d) { opb.template issue<H * ((QB + 1) / 2) + decltype(d)::value>(stage_off); });
-    };
+    using Plan = LoadPlan<QA, QB, OpA::PAIR, OpB::PAIR, NS>;
+    constexpr int LAG = Plan::LAG;
     auto next_stage = [&](uint32_t off) -> uint32_t { return off + SB == RING ? 0u : off + SB; };
 
-    // ---- prologue: K-steps 0..NS-2 in flight, step 0 visible, its first fragments on their way --
-    uint32_t st_load = 0;   // stage that receives the next K-step to be fetched
-    static_for<NS - 1>([&](auto) {
-        load_cluster_a(Int<0>{}, st_load);
-        load_cluster_a(Int<1>{}, st_load);
-        load_cluster_b(Int<0>{}, st_load);
-        load_cluster_b(Int<1>{}, st_load);
-        opa.advance();
-        opb.advance();
-        st_load += SB;
+    // ---- prologue: the loads "steps -(NS-1) .. -1" would have issued; K-step 0 visible ----------
+    static_for<NS - 1>([&](auto v) {
+        constexpr int T = decltype(v)::value - (NS - 1);          // virtual step
+        constexpr uint32_t FAR = (T + NS - 1) * SB;               // stage of K-step T+NS-1
+        static_for<2>([&](auto op_c) {
+            constexpr bool IS_A = decltype(op_c)::value == 0;
+            using Op = typename std::conditional<IS_A, OpA, OpB>::type;
+            auto& op = [&]() -> auto& { if constexpr (IS_A) return opa; else return opb; }();
+            if constexpr (Op::PAIR && T == -(NS - 1)) {
+                // K-step -1 does not exist: only the K-step 0 half of the pair, window stays
+                static_for<Op::NBASE>([&](auto d) { op.template issue<decltype(d)::value, 0>(FAR); });
+                op.flip();
+            } else {
+                constexpr uint32_t NEAR = Op::PAIR ? FAR - SB : 0u;
+                issue_loads(op_c, Int<2>{}, Int<0>{}, NEAR, FAR);
+                issue_loads(op_c, Int<2>{}, Int<1>{}, NEAR, FAR);
+                op.advance();
+            }
+        });
     });
-    wait_vmcnt<(NS - 2) * NL>();
+    wait_vmcnt<(NS - LAG + 1) * NL>();
     __builtin_amdgcn_s_barrier();
     AXONN_FENCE();
     uint32_t st_cur = 0, st_next = SB;
+    uint32_t st_near = (NS - 2) * SB, st_far = (NS - 1) * SB;   // stages of K-steps t+NS-2 and t+NS-1
     // read cursors of the current stage; the ones of the next stage are made in the second half of
     // a step and become the current ones when the step ends
     typename OpA::Cursor ca = opa.cursor(st_cur);
     typename OpB::Cursor cb = opb.cursor(st_cur);
 
     // ---- one K-step on the stage at st_cur ---------------------------------------------------
-    //   LOAD: also fetch K-step t+NS-1 into the stage at st_load (the one step t-1 used).
+    //   KIND: what it fetches (see above).
     //   NEXT: a following K-step exists.
     //   VM:   direct loads that may still be in flight at the barrier (everything older has
     //         landed, in particular the whole of K-step t+1).
     //   PHASE: where the two clusters of a half sit among its NM MFMAs.  With two waves per SIMD the
     //         second wave of each SIMD (waves 4..7) uses phase 1, so that one wave's clusters fall
     //         into the other's runs of MFMAs and the matrix pipe always has work queued.
-    auto step = [&](auto phase_c, auto load_c, auto next_c, auto vm_c) {
-        constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value;
-        constexpr int VM = decltype(vm_c)::value;
+    auto step = [&](auto phase_c, auto kind_c, auto next_c, auto vm_c) {
+        constexpr bool NEXT = decltype(next_c)::value;
+        constexpr int VM = decltype(vm_c)::value, KIND = decltype(kind_c)::value;
         constexpr int P0 = decltype(phase_c)::value == 0 ? 1 : NM / 4 + 1;        // MFMAs before cluster 0
         constexpr int P1 = decltype(phase_c)::value == 0 ? NM / 2 + 1 : NM / 4 + NM / 2 + 1;   // ... cluster 1
         // first half: MFMAs of substep 0 (buffer 0); substep-1 fragments into buffer 1
@@ -471,12 +577,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         mfma_range(Int<0>{}, Int<0>{}, Int<P0>{});
         AXONN_FENCE();
         read_cluster(Int<0>{}, Int<1>{}, Int<1>{}, ca, cb);
-        if constexpr (LOAD) load_cluster_a(Int<0>{}, st_load);
+        issue_loads(Int<0>{}, kind_c, Int<0>{}, st_near, st_far);
         AXONN_FENCE();
         mfma_range(Int<0>{}, Int<P0>{}, Int<P1>{});
         AXONN_FENCE();
         read_cluster(Int<1>{}, Int<1>{}, Int<1>{}, ca, cb);
-        if constexpr (LOAD) load_cluster_a(Int<1>{}, st_load);
+        issue_loads(Int<0>{}, kind_c, Int<1>{}, st_near, st_far);
         AXONN_FENCE();
         mfma_range(Int<0>{}, Int<P1>{}, Int<NM>{});
         AXONN_FENCE();
@@ -495,26 +601,30 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
             cb = opb.cursor(st_next);
             read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
         }
-        if constexpr (LOAD) load_cluster_b(Int<0>{}, st_load);
+        issue_loads(Int<1>{}, kind_c, Int<0>{}, st_near, st_far);
         AXONN_FENCE();
         mfma_range(Int<1>{}, Int<P0>{}, Int<P1>{});
         AXONN_FENCE();
         if constexpr (NEXT) read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
-        if constexpr (LOAD) {
-            load_cluster_b(Int<1>{}, st_load);
+        issue_loads(Int<1>{}, kind_c, Int<1>{}, st_near, st_far);
+        if constexpr (KIND == 2) {
             opa.advance();
             opb.advance();
         }
         AXONN_FENCE();
         mfma_range(Int<1>{}, Int<P1>{}, Int<NM>{});
         AXONN_FENCE();
-        st_load = st_cur;   // the stage just finished is the next one to refill
+        st_near = st_far;
+        st_far = st_cur;   // the stage just finished is the last one of the ring to be refilled
         st_cur = st_next;
         st_next = next_stage(st_next);
     };
     using Yes = std::true_type;
     using No = std::false_type;
 
+    // After KT-NS+1 full steps come the steps that fetch less: one of kind 1 if an operand is
+    // paired (K-step KT-1 still lacks that operand's other half), then kind 0 to the end.
+    constexpr int NTAIL = NS - 1;
     const int KT = ktotal / KB;   // at least NS - 1
     auto main_loop = [&](auto phase_c) {
         // The first fragments are fetched here, inside the phase's own code path: an LDS read is
@@ -523,11 +633,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         // destination registers.
         read_cluster(Int<0>{}, Int<0>{}, Int<0>{}, ca, cb);
         read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
-        // steady state: in flight at the barrier are K-steps t+2 .. t+NS-2 and the A part of t+NS-1
-        for (int kt = 0; kt + (NS - 1) < KT; ++kt) step(phase_c, Yes{}, Yes{}, Int<(NS - 3) * NL + QA>{});
-        // drain: nothing left to fetch; K-steps t+2 .. KT-1 may still be in flight at the barrier
-        static_for<NS - 2>([&](auto j) { step(phase_c, No{}, Yes{}, Int<(NS - 3 - decltype(j)::value) * NL>{}); });
-        step(phase_c, No{}, No{}, Int<0>{});
+        constexpr int VM_FULL = Plan::tail_vm(-1);
+        for (int kt = KT - NTAIL; kt > 0; --kt) step(phase_c, Int<2>{}, Yes{}, Int<VM_FULL>{});
+        static_for<NTAIL>([&](auto j_c) {
+            constexpr int J = decltype(j_c)::value;
+            step(phase_c, Int<Plan::tail_kind(J)>{}, std::integral_constant<bool, (J + 1 < NTAIL)>{},
+                 Int<Plan::tail_vm(J)>{});
+        });
     };
     if constexpr (NW == 8) {
         if (wave >= 4) main_loop(Int<1>{});   // wave-uniform; both paths hit the same barriers
