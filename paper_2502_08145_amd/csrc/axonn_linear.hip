@@ -179,9 +179,9 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
     static const double eff[3][8] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, then the 8-wave 256x256 256x128 128x256 */
-        /* NN */ {0.0, 1.00, 0.78, 0.90, 0.72, 1.06, 0.80, 0.93},
-        /* NT */ {0.0, 1.00, 0.74, 0.75, 0.68, 0.99, 0.76, 0.74},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.75, 1.05, 0.92, 0.96},
+        /* NN */ {0.0, 1.00, 0.83, 0.86, 0.77, 1.06, 0.82, 0.86},
+        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95},
     };
     constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0;
     int best = 0;
@@ -191,12 +191,15 @@ static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allo
         if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split)) continue;
         const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
         // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
-        // side by side at half speed each, which comes to the same).
-        const int64_t rounds = (wgs + 255) / 256;
-        if (var.splits > 1 && rounds > 1) continue;   // readers and writers of a tile run side by side
+        // side by side at half speed each, which comes to the same).  A last round that fills only
+        // a fraction f of the CUs runs faster than a full one (the busy CUs get the idle ones'
+        // power and bandwidth): measured about 0.5 + 0.5 f of a full round.
+        const int64_t full = wgs / 256, rest = wgs % 256;
+        if (var.splits > 1 && full + (rest ? 1 : 0) > 1) continue;   // readers and writers of a tile run side by side
+        const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
         const double k_cost = (double)(K / var.splits) +
                               (var.splits == 1 ? kFixedK : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
-        const double t = (double)rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
+        const double t = rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
         if (best == 0 || t < best_t) {
             best = v;
             best_t = t;
