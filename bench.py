@@ -151,7 +151,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+            from paper_2502_08145_amd.profile_summary import kernel_key
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(kernel_key(*dom.split("/")))
         except Exception:
             traffic = None
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

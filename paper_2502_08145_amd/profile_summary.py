@@ -1,9 +1,13 @@
 """Turn rocprofv3 CSV output into a short text summary (per kernel: calls, mean duration,
-counter means, HBM bytes scaled by the copy probe).
+counter means) and, on request, into the HBM bytes per launch that bench.py reports.
 
     python -m paper_2502_08145_amd.profile_summary <dir> [<dir> ...]
+    python -m paper_2502_08145_amd.profile_summary --traffic <workload> <copy MiB> <FETCH dir> <WRITE dir>
 
 Each <dir> is the -d directory of one rocprofv3 run (--kernel-trace, with --stats and/or --pmc).
+--traffic prints a JSON object {workload: {kernel: bytes per launch}}: FETCH_SIZE and WRITE_SIZE
+(KiB per dispatch) of every GEMM kernel, each scaled by what the same counter read for the copy
+probe of <copy MiB> MiB that ran in the same process (bench.py --calibrate-copy).
 """
 from __future__ import annotations
 
@@ -16,11 +20,12 @@ import sys
 
 
 def short(name: str) -> str:
-    m = re.search(r"gemm_tile_kernel<(\d+), (\d+), (true|false), (true|false)>", name)
+    m = re.search(r"gemm_tile_kernel<(\d+), (\d+), (\d+), (\d+), (true|false), (true|false), (true|false)>", name)
     if m:
-        bm, bn, akc, bkc = m.groups()
+        bm, bn, wm, wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
-        return f"mfma_{bm}x{bn}/{lay}"
+        waves = "_w8" if int(wm) * int(wn) == 8 else ""
+        return f"mfma_{bm}x{bn}{waves}{'_sk' if split == 'true' else ''}/{lay}"
     if "copy_probe_kernel" in name:
         return "copy_probe"
     if "gemm_naive_kernel" in name:
@@ -50,9 +55,37 @@ def summarize(d: str, out=sys.stdout):
     return dur, ctr
 
 
+def kernel_key(variant: str, layout: str) -> str:
+    """The name this module gives the kernel behind a library variant (split-K variants of 2 and
+    4 K ranges are one kernel)."""
+    return re.sub(r"_sk\d+$", "_sk", variant) + "/" + layout
+
+
+def traffic(workload: str, copy_mib: float, fetch_dir: str, write_dir: str) -> dict:
+    import io
+    _, fetch = summarize(fetch_dir, io.StringIO())
+    _, write = summarize(write_dir, io.StringIO())
+    mean = lambda v: sum(v) / len(v)
+    kib = copy_mib * 1024.0
+    f_scale = kib / mean(fetch["copy_probe"]["FETCH_SIZE"])
+    w_scale = kib / mean(write["copy_probe"]["WRITE_SIZE"])
+    out = {}
+    for k in fetch:
+        if k.startswith("mfma_") and k in write:
+            out[k] = int(round(1024.0 * (mean(fetch[k]["FETCH_SIZE"]) * f_scale + mean(write[k]["WRITE_SIZE"]) * w_scale)))
+    return {workload: out, "_scale": {"FETCH_SIZE": round(f_scale, 4), "WRITE_SIZE": round(w_scale, 4)},
+            "_note": "bytes per launch = FETCH_SIZE x scale + WRITE_SIZE x scale (KiB -> bytes), scales from the copy probe"}
+
+
 def main(argv):
     if len(argv) < 2:
         sys.exit(__doc__)
+    if argv[1] == "--traffic":
+        import json
+        if len(argv) != 6:
+            sys.exit(__doc__)
+        print(json.dumps(traffic(argv[2], float(argv[3]), argv[4], argv[5]), indent=1))
+        return
     for d in argv[1:]:
         summarize(d)
 
