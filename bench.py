@@ -133,8 +133,10 @@ def main():
     for gi, g in enumerate(gemms):
         ms = float(np.mean([ev[s][gi][0].elapsed_time(ev[s][gi][1]) for s in range(args.steps)]))
         per.append(ms)
+        alg_bytes = 2.0 * (g["M"] * g["K"] + g["K"] * g["N"] + g["M"] * g["N"])   # A, B read once, C written once
         log(f"  {g['name']:<22s} {g['layout']} M={g['M']:<6d} N={g['N']:<6d} K={g['K']:<6d} {g['variant']:<20s} "
-            f"{ms * 1e3:8.1f} us  {g['flops'] / ms / 1e9:7.1f} TFLOP/s  {g['flops'] / ms / 1e9 / PEAK_BF16_TFLOPS * 100:5.1f}%")
+            f"{ms * 1e3:8.1f} us  {g['flops'] / ms / 1e9:7.1f} TFLOP/s  {g['flops'] / ms / 1e9 / PEAK_BF16_TFLOPS * 100:5.1f}%"
+            f"  {alg_bytes / ms / 1e6:6.0f} GB/s alg.")
     for g in gemms:
         if not torch.isfinite(g["c"].float()).all():
             sys.exit(f"bench.py: non-finite output in {g['name']}")

@@ -40,7 +40,9 @@
  *              which exchange fp32 partial tiles through a scratch area owned by
  *              the library: 64 MiB of device memory per GPU, allocated (hipMalloc)
  *              by axonn_linear_init or by the first call that needs it, and kept
- *              until the process ends.  If it cannot be had the other kernels run.
+ *              until the process ends -- or memory of the caller's, registered with
+ *              axonn_linear_set_workspace, in which case the library never
+ *              allocates.  If no area can be had the other kernels run.
  *              Calls that may EXECUTE CONCURRENTLY on one GPU (different streams)
  *              would share it: serialise them or switch split-K off
  *              (axonn_linear_set_split_k).  Calls on one stream are always safe.
@@ -81,7 +83,8 @@ enum {
     AXONN_OK = 0,
     AXONN_ERR_INVALID_ARG = -1, /* null / misaligned pointer, negative or oversized dim, bad enum or flag */
     AXONN_ERR_UNSUPPORTED = -2, /* a forced kernel variant cannot run this shape */
-    AXONN_ERR_LAUNCH = -3       /* the HIP runtime refused the launch */
+    AXONN_ERR_LAUNCH = -3,      /* the HIP runtime refused the launch */
+    AXONN_ERR_WORKSPACE = -4    /* a forced split-K variant has no scratch area (allocation failed / workspace too small) */
 };
 
 /* Forward, Algorithm 1 line 3:  Y[M,N] = X * W.  X and W stored as `layout` says. */
@@ -111,10 +114,21 @@ const char *axonn_status_string(int status);
 /* Library version, major * 10000 + minor * 100 + patch. */
 int axonn_linear_version(void);
 
+/* Caller-owned split-K scratch.  axonn_linear_workspace_bytes: what the kernel the library would
+ * pick for this problem needs (0: none).  axonn_linear_set_workspace: use `bytes` bytes at the
+ * DEVICE pointer `dev_ptr` (256-byte aligned) as the current device's scratch area from now on; the
+ * first 4 KiB are cleared (synchronously).  The caller keeps ownership and must keep the memory
+ * alive, and untouched, while it is registered; NULL / 0 unregisters it.  A problem whose need
+ * exceeds the registered size runs without split-K.  Must not be called while GEMM calls are in
+ * flight on that device.  AXONN_OK, AXONN_ERR_INVALID_ARG, or AXONN_ERR_WORKSPACE if `bytes` cannot
+ * hold a single tile (4 KiB + 256 KiB). */
+size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout);
+int axonn_linear_set_workspace(void *dev_ptr, size_t bytes);
+
 /* Optional set-up for the current device: raises the kernels' LDS limits and allocates the split-K
  * scratch area now rather than inside the first call that needs it (do this before capturing calls
  * into a HIP graph: an allocation is not allowed during capture).  Idempotent.  AXONN_OK, or
- * AXONN_ERR_LAUNCH if the allocation failed (the library then works without split-K). */
+ * AXONN_ERR_WORKSPACE if the allocation failed (the library then works without split-K). */
 int axonn_linear_init(void);
 
 /* Allow (1, the default) or forbid (0) the automatic choice of split-K kernels, process-wide.

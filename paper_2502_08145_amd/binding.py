@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libaxonn_linear.so")
 
 AXONN_NN, AXONN_NT, AXONN_TN = 0, 1, 2
 LAYOUTS = {"NN": AXONN_NN, "NT": AXONN_NT, "TN": AXONN_TN}
-AXONN_OK, AXONN_ERR_INVALID_ARG, AXONN_ERR_UNSUPPORTED, AXONN_ERR_LAUNCH = 0, -1, -2, -3
+AXONN_OK, AXONN_ERR_INVALID_ARG, AXONN_ERR_UNSUPPORTED, AXONN_ERR_LAUNCH, AXONN_ERR_WORKSPACE = 0, -1, -2, -3, -4
 
 EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
@@ -25,6 +25,7 @@ EXPORTS = (
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
     "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
+    "axonn_linear_workspace_bytes", "axonn_linear_set_workspace",
 )
 
 _lib = None
@@ -68,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_copy_probe.restype = ci
         L.axonn_linear_mfma_probe.argtypes = [vp, ctypes.c_size_t, ci, ci, vp, vp]
         L.axonn_linear_mfma_probe.restype = ci
+        L.axonn_linear_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.axonn_linear_workspace_bytes.restype = ctypes.c_size_t
+        L.axonn_linear_set_workspace.argtypes = [vp, ctypes.c_size_t]
+        L.axonn_linear_set_workspace.restype = ci
         L.axonn_linear_init.argtypes = []
         L.axonn_linear_init.restype = ci
         L.axonn_linear_set_split_k.argtypes = [ci]
@@ -114,6 +119,25 @@ def axonn_linear_init() -> None:
     rc = lib().axonn_linear_init()
     if rc != 0:
         raise AxonnError(rc, "axonn_linear_init")
+
+
+def axonn_linear_workspace_bytes(M: int, N: int, K: int, layout) -> int:
+    """Split-K scratch bytes the automatically chosen kernel needs for this problem (0: none)."""
+    return int(lib().axonn_linear_workspace_bytes(M, N, K, _layout(layout)))
+
+
+def axonn_linear_set_workspace(buf, check=True) -> int:
+    """Register a device buffer (a torch tensor, kept alive by the caller) as the split-K scratch
+    area of the current device; None unregisters it."""
+    if buf is None:
+        rc = lib().axonn_linear_set_workspace(None, 0)
+    else:
+        if not buf.is_cuda or not buf.is_contiguous():
+            raise TypeError("expected a contiguous CUDA tensor")
+        rc = lib().axonn_linear_set_workspace(buf.data_ptr(), buf.numel() * buf.element_size())
+    if check and rc != 0:
+        raise AxonnError(rc, "axonn_linear_set_workspace")
+    return rc
 
 
 def axonn_linear_set_split_k(enable: bool) -> bool:

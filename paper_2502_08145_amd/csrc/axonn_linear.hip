@@ -116,42 +116,61 @@ static const Variant g_variants[] = {
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
-// Split-K scratch: one area per device, allocated on first need and kept until the process ends.
-constexpr int kScratchSlots = 256;                          // slots of one 256x256 fp32 tile
+// Split-K scratch: one area per device.  Layout: kFlagBytes of flags (one 32-bit flag per slot, the
+// time-out counter in the last word), then `slots` slots of one 256x256 fp32 tile.  Either the
+// caller's (axonn_linear_set_workspace) or the library's own, allocated on first need and kept until
+// the process ends.
+constexpr int kScratchSlots = 256;                          // the most any variant is allowed to need
 constexpr size_t kSlotBytes = 256 * 256 * sizeof(float);
+constexpr size_t kFlagBytes = 4096;                         // 1023 flags + the counter
 constexpr int kMaxDevices = 64;
 struct Scratch {
     float* partials = nullptr;
-    uint32_t* flags = nullptr;      // kScratchSlots flags, then the time-out counter
+    uint32_t* flags = nullptr;
+    int slots = 0;
+    void* owned = nullptr;          // the library's own allocation, if it made one
+    uint32_t* timeouts() const { return flags + kFlagBytes / sizeof(uint32_t) - 1; }
 };
 static Scratch g_scratch[kMaxDevices];
 static std::mutex g_scratch_mutex;
 static std::atomic<uint32_t> g_epoch{0};
 static std::atomic<int> g_split_k_enabled{1};
 
-// The current device's scratch area, or nullptr if it cannot be had.
-static const Scratch* get_scratch() {
+static bool adopt(Scratch& sc, void* p, size_t bytes) {
+    if (bytes < kFlagBytes + kSlotBytes) return false;
+    if (hipMemset(p, 0, kFlagBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    size_t slots = (bytes - kFlagBytes) / kSlotBytes;
+    if (slots > (size_t)kScratchSlots) slots = kScratchSlots;
+    sc.flags = static_cast<uint32_t*>(p);
+    sc.partials = reinterpret_cast<float*>(static_cast<char*>(p) + kFlagBytes);
+    sc.slots = (int)slots;
+    return true;
+}
+
+// The current device's scratch area (by value: a later set_workspace does not disturb a launch being
+// prepared), with at least `slots_needed` slots; .partials == nullptr if that cannot be had.
+static Scratch get_scratch(int slots_needed) {
     int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Scratch{};
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
     Scratch& sc = g_scratch[dev];
     if (!sc.partials) {
         void* p = nullptr;
-        const size_t flag_bytes = (kScratchSlots + 64) * sizeof(uint32_t);
-        if (hipMalloc(&p, kScratchSlots * kSlotBytes + flag_bytes) != hipSuccess) {
+        const size_t bytes = kFlagBytes + kScratchSlots * kSlotBytes;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
             (void)hipGetLastError();
-            return nullptr;
+            return Scratch{};
         }
-        uint32_t* flags = reinterpret_cast<uint32_t*>(static_cast<char*>(p) + kScratchSlots * kSlotBytes);
-        if (hipMemset(flags, 0, flag_bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-            (void)hipGetLastError();
+        if (!adopt(sc, p, bytes)) {
             (void)hipFree(p);
-            return nullptr;
+            return Scratch{};
         }
-        sc.flags = flags;
-        sc.partials = static_cast<float*>(p);
+        sc.owned = p;
     }
-    return &sc;
+    return sc.slots >= slots_needed ? sc : Scratch{};
 }
 
 static std::atomic<int> g_forced{-1};
@@ -240,13 +259,18 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     if (M == 0 || N == 0) return AXONN_OK;
 
     int v = g_forced.load(std::memory_order_relaxed);
-    const Scratch* scratch = nullptr;
+    Scratch scratch;
+    auto slots_needed = [&](int variant) {
+        const Variant& x = g_variants[variant];
+        return (int)((M / x.bm) * (N / x.bn) * (x.splits - 1));
+    };
     if (v >= 0) {
         if (!variant_supports(v, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch())) return AXONN_ERR_LAUNCH;
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch(slots_needed(v))).partials) return AXONN_ERR_WORKSPACE;
     } else {
         v = select_variant(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch())) v = select_variant(M, N, K, layout, false);
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch(slots_needed(v))).partials)
+            v = select_variant(M, N, K, layout, false);
     }
     const Variant& var = g_variants[v];
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -273,7 +297,7 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
         if (var.splits > 1) {
             uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
             if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;   // flags start at 0
-            sk = SplitK{scratch->partials, scratch->flags, scratch->flags + kScratchSlots, epoch, var.splits};
+            sk = SplitK{scratch.partials, scratch.flags, scratch.timeouts(), epoch, var.splits};
         }
         hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)(tiles * var.splits)), dim3(var.threads), var.lds_bytes, s,
                            A, B, C, (int)M, (int)N, (int)K, tiles_m, tiles_n, group_m, sk);
@@ -306,6 +330,7 @@ const char* axonn_status_string(int status) {
         case AXONN_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad dimension, layout or flag)";
         case AXONN_ERR_UNSUPPORTED: return "the forced kernel variant cannot run this shape";
         case AXONN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case AXONN_ERR_WORKSPACE: return "no split-K scratch area (allocation failed or the registered workspace is too small)";
         default: return "unknown status";
     }
 }
@@ -329,7 +354,32 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
 
 int axonn_linear_init(void) {
     std::call_once(axonn::g_attr_once, axonn::raise_lds_limits);
-    return axonn::get_scratch() ? AXONN_OK : AXONN_ERR_LAUNCH;
+    return axonn::get_scratch(1).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
+}
+
+size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout) {
+    if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return 0;
+    const int v = axonn::select_variant(M, N, K, layout, true);
+    const axonn::Variant& var = axonn::g_variants[v];
+    if (var.splits == 1) return 0;
+    return axonn::kFlagBytes + (size_t)((M / var.bm) * (N / var.bn) * (var.splits - 1)) * axonn::kSlotBytes;
+}
+
+int axonn_linear_set_workspace(void* dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0) || (reinterpret_cast<uintptr_t>(dev_ptr) & 255)) return AXONN_ERR_INVALID_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= axonn::kMaxDevices) return AXONN_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
+    axonn::Scratch& sc = axonn::g_scratch[dev];
+    if (dev_ptr == nullptr) {            // back to a library-owned area (made on next need)
+        if (!sc.owned) sc = axonn::Scratch{};
+        return AXONN_OK;
+    }
+    axonn::Scratch fresh;
+    if (!axonn::adopt(fresh, dev_ptr, bytes)) return AXONN_ERR_WORKSPACE;
+    if (sc.owned) (void)hipFree(sc.owned);   // no launch may be in flight (documented)
+    sc = fresh;
+    return AXONN_OK;
 }
 
 int axonn_linear_set_split_k(int enable) {
@@ -345,7 +395,7 @@ int axonn_linear_split_k_timeouts(uint64_t* count) {
     uint32_t* counter = nullptr;
     {
         std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
-        if (axonn::g_scratch[dev].flags) counter = axonn::g_scratch[dev].flags + axonn::kScratchSlots;
+        if (axonn::g_scratch[dev].flags) counter = axonn::g_scratch[dev].timeouts();
     }
     if (!counter) return AXONN_OK;   // no split-K kernel has run on this device
     uint32_t v = 0;

@@ -1,21 +1,24 @@
-// bf16 x bf16 -> fp32 -> bf16 GEMM tile kernel for gfx950 (CDNA4): one output tile per workgroup.
+// bf16 x bf16 -> fp32 -> bf16 GEMM tile kernel for gfx950 (CDNA4): one output tile per workgroup
+// (or per `splits` workgroups, each over one K range).
 //
 //   C[M,N] = sum_k a(i,k) b(k,j)      (the local matrix multiply of Algorithm 1 lines 3, 11, 13)
 //
 // How the kernel is put together, in the order data moves:
 //
-//  * 4 waves (one per SIMD) own a BM x BN output tile as a 2 x 2 grid of (BM/2) x (BN/2) wave
-//    tiles; the accumulators (up to 256 fp32 per lane) never leave the register file.
+//  * 4 waves (one per SIMD, 2 x 2) or 8 waves (two per SIMD, 2 x 4) own a BM x BN output tile;
+//    the accumulators (up to 256 fp32 per lane) never leave the register file.
 //  * K is consumed 32 at a time.  The operand panels of a K-step live in one stage of an LDS ring
-//    of NS stages (as many as fit in 160 KB: 5 for the 256x256 tile); the panels of step t+NS-1
-//    are fetched while step t is multiplied.  Global memory goes
-//    STRAIGHT into LDS (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging, no LDS store
-//    instruction); the loads of a stage are spread over a whole K-step, a few per cluster.
+//    of NS stages (as many as fit in 160 KB: 5 for the 256x256 tile); panels are fetched NS-2 and
+//    NS-1 K-steps ahead of their use.  Global memory goes STRAIGHT into LDS
+//    (global_load_lds_dwordx4: 16 bytes per lane, no VGPR staging, no LDS store instruction); the
+//    loads of a K-step are spread over the whole step, a few per cluster.
 //  * An operand is either "K-contiguous" in global memory (A of NN/NT, B of NT) or
 //    "MN-contiguous" (A of TN, B of NN/TN):
 //      - K-contiguous panels sit in LDS as rows of 32 k (64 bytes) with the four 16-byte chunks
 //        of a row XOR-swizzled by (row>>2)&3, and are read with ds_read_b128: lane l gets, for
-//        row l%32, the eight k values 8*(l/32)..+7 that v_mfma_f32_32x32x16_bf16 wants.
+//        row l%32, the eight k values 8*(l/32)..+7 that v_mfma_f32_32x32x16_bf16 wants.  Their
+//        loads go out in pairs (two K-steps of the same rows back to back) so that both halves of
+//        every 128-byte cache line are fetched together.
 //      - MN-contiguous panels sit in LDS exactly as in memory, one LDS row per k, with the 16-byte
 //        chunks of k-row k XOR-swizzled by 4*(k&3), and are read with the transposing
 //        ds_read_b64_tr_b16 (two per fragment).  No register transposes anywhere.
@@ -30,9 +33,10 @@
 //    base plus one VGPR offset that advances once per K-step.  Loads and LDS reads are inline
 //    asm (the compiler would otherwise re-derive addresses with VALU instructions and pick the
 //    64-bit-VGPR addressing form); the waits on them are therefore written out by hand too.
+//    With two waves per SIMD the second wave's clusters are shifted into the first one's MFMA runs.
 //  * One barrier per K-step, placed in the MIDDLE of the step's MFMAs: by then the next stage has
 //    landed (vmcnt) and this stage's last fragments are in registers, so the barrier both
-//    publishes stage t+1 and releases stage t for the loads of step t+NS.
+//    publishes stage t+1 and releases stage t for refilling.
 //  * MFMAs are issued as mfma(Bfrag, Afrag): the 32x32 result block then holds, in lane l, column
 //    m = l%32 and FOUR CONSECUTIVE n per accumulator quad, so the epilogue packs 4 bf16 into one
 //    8-byte LDS store, transposes the tile through LDS and writes C with 16-byte coalesced

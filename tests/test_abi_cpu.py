@@ -104,3 +104,17 @@ def test_variant_table_and_selection():
     with pytest.raises(B.AxonnError):
         B.force_variant(n)
     B.force_variant(-1)
+
+
+def test_workspace_queries_are_host_only():
+    # split-K problems need 4 KiB of flags plus one fp32 tile per (tile, extra K range)
+    assert B.axonn_linear_workspace_bytes(2048, 4096, 16384, "NT") == 4096 + 128 * 256 * 256 * 4
+    assert B.axonn_linear_workspace_bytes(2048, 2048, 8192, "NN") == 4096 + 64 * 3 * 256 * 256 * 4
+    assert B.axonn_linear_workspace_bytes(8192, 8192, 8192, "TN") == 0
+    assert B.axonn_linear_workspace_bytes(100, 200, 300, "NN") == 0
+    assert B.axonn_linear_workspace_bytes(0, 8, 8, "NN") == 0
+    L = B.lib()
+    assert L.axonn_linear_set_workspace(0x1000, 0) == B.AXONN_ERR_INVALID_ARG      # pointer without size
+    assert L.axonn_linear_set_workspace(None, 4096) == B.AXONN_ERR_INVALID_ARG     # size without pointer
+    assert L.axonn_linear_set_workspace(0x1010, 1 << 20) == B.AXONN_ERR_INVALID_ARG  # not 256-byte aligned
+    assert "scratch" in B.status_string(B.AXONN_ERR_WORKSPACE)

@@ -156,6 +156,45 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
             U.assert_close(got, ref, f"{B.variant_name(v)} {layout} K={K}")
 
 
+def test_caller_owned_workspace(oracle_mod):
+    # the same split-K problem through the library's own scratch area, through a registered buffer
+    # that is large enough, and with one that is too small (automatic choice then avoids split-K,
+    # a forced split-K variant is refused)
+    M, N, K, layout = 512, 1024, 1792, "NT"
+    a = synth.integer_bf16(93, (M, K), -4, 4)
+    b = synth.integer_bf16(94, (K, N), -4, 4)
+    A, Bm = store(a, b, layout)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
+    sk2 = next(v for v in tile_variants() if B.variant_name(v) == "mfma_256x256_w8_sk2")
+    need = 4096 + 8 * 256 * 256 * 4
+    try:
+        big = torch.full((need + 4096,), 0x55, dtype=torch.uint8, device="cuda")     # dirty on purpose
+        B.axonn_linear_set_workspace(big)
+        for rep in range(2):
+            assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=sk2), want)
+        small = torch.zeros((4096 + 3 * 256 * 256 * 4,), dtype=torch.uint8, device="cuda")
+        B.axonn_linear_set_workspace(small)
+        B.force_variant(sk2)
+        try:
+            c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            rc = B.axonn_linear_fwd(M, N, K, layout, U.to_device(A), U.to_device(Bm), c, check=False)
+            assert rc == B.AXONN_ERR_WORKSPACE
+        finally:
+            B.force_variant(-1)
+        # automatic selection for a split-K-worthy shape still gives the right answer
+        M2, N2, K2 = 1024, 1024, 4096
+        a2 = synth.integer_bf16(95, (M2, K2), -4, 4)
+        b2 = synth.integer_bf16(96, (K2, N2), -4, 4)
+        A2, B2 = store(a2, b2, layout)
+        assert B.axonn_linear_workspace_bytes(M2, N2, K2, layout) > small.numel()
+        want2 = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M2, N2, K2, layout, A2, B2))
+        assert np.array_equal(run_gpu("fwd", M2, N2, K2, layout, A2, B2), want2)
+    finally:
+        B.axonn_linear_set_workspace(None)
+    assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=sk2), want)
+    assert B.axonn_linear_split_k_timeouts() == 0
+
+
 # ------------------------------------------------------------------ exact integers: bit for bit
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_integer_inputs_are_bit_exact(oracle_mod, layout):
