@@ -1,4 +1,4 @@
-"""CPU oracle for the FC-layer matrix multiplies (TEST INFRASTRUCTURE ONLY).
+"""CPU oracle for the FC-layer matrix multiplies and their operand re-storage (TEST INFRASTRUCTURE ONLY).
 
 Nothing in the product imports this package.  Only the tests, the smoke check
 and the benchmark's cpu_baseline leg may call it.  It shares no code with the
@@ -13,4 +13,5 @@ from .reference import (  # noqa: F401
     linear_bwd_data,
     linear_bwd_weight,
     max_threads,
+    transpose,
 )

@@ -22,6 +22,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
+_SRC_T = os.path.join(_HERE, "transpose_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_oracle.so")
 
 LAYOUTS = {"NN": 0, "NT": 1, "TN": 2}
@@ -31,9 +32,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (no GPU toolchain involved)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_T))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-fopenmp", "-std=c11", "-shared", "-fPIC",
-               "-Wall", "-Wextra", _SRC, "-o", _LIB]
+               "-Wall", "-Wextra", _SRC, _SRC_T, "-o", _LIB]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -49,6 +51,8 @@ def _load():
         lib.oracle_gemm_bf16_f64_at.argtypes = [i64, i64, i64, ctypes.c_int, p, p, i64, p, p, p,
                                                 ctypes.c_int]
         lib.oracle_gemm_bf16_f64_at.restype = ctypes.c_int
+        lib.oracle_transpose_u16.argtypes = [i64, i64, p, p]
+        lib.oracle_transpose_u16.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -134,3 +138,16 @@ def linear_bwd_weight(M, N, K, layout, X, dY, threads=None):
     and dL/dO ([tokens,out] = [K,N]) the mode is TN.
     """
     return gemm(M, N, K, layout, X, dY, threads)
+
+
+def transpose(bits: np.ndarray) -> np.ndarray:
+    """The operand re-stored for another mode (Sec. IV-C): [rows, cols] -> [cols, rows], bit patterns moved."""
+    if not isinstance(bits, np.ndarray) or bits.dtype != np.uint16 or bits.ndim != 2:
+        raise TypeError("expected a 2-D numpy uint16 array of bf16 bit patterns")
+    src = np.ascontiguousarray(bits)
+    rows, cols = src.shape
+    dst = np.empty((cols, rows), dtype=np.uint16)
+    rc = _load().oracle_transpose_u16(rows, cols, src.ctypes.data, dst.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_transpose_u16 failed ({rc})")
+    return dst

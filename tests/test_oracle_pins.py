@@ -288,3 +288,39 @@ def test_empty_and_bad_arguments(oracle_mod):
         oracle_mod.gemm(2, 3, 4, "TT", np.zeros((2, 4), np.uint16), b)
     with pytest.raises(RuntimeError):
         oracle_mod.gemm_at(2, 3, 4, "NN", np.zeros((2, 4), np.uint16), b, [2], [0])
+
+
+# ------------------------------------------------------------------ operand re-storage (Sec. IV-C)
+def test_transpose_hand_example_and_shapes(oracle_mod):
+    # worked by hand from the definition dst[c][r] = src[r][c]
+    src = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.uint16)
+    assert oracle_mod.transpose(src).tolist() == [[1, 4], [2, 5], [3, 6]]
+    row = np.arange(7, dtype=np.uint16).reshape(1, 7)
+    assert oracle_mod.transpose(row).tolist() == [[v] for v in range(7)]
+    assert oracle_mod.transpose(oracle_mod.transpose(row)).tolist() == row.tolist()
+    assert oracle_mod.transpose(np.zeros((0, 5), np.uint16)).shape == (5, 0)
+    with pytest.raises(TypeError):
+        oracle_mod.transpose(np.zeros((2, 2), np.float32))
+
+
+@pytest.mark.parametrize("shape", [(3, 5), (64, 64), (65, 130), (257, 31), (1000, 8)])
+def test_transpose_position_code_involution_and_numpy(oracle_mod, shape):
+    rows, cols = shape
+    # every element carries its own (row, col): a wrong index map cannot pass
+    src = ((np.arange(rows)[:, None] * 251 + np.arange(cols)[None, :] * 7) % 65521).astype(np.uint16)
+    dst = oracle_mod.transpose(src)
+    assert dst.shape == (cols, rows)
+    for r, c in [(0, 0), (rows - 1, 0), (0, cols - 1), (rows - 1, cols - 1), (rows // 2, cols // 3)]:
+        assert dst[c, r] == src[r, c]
+    assert np.array_equal(dst, src.T)                       # the library routine it must reduce to
+    assert np.array_equal(oracle_mod.transpose(dst), src)   # involution
+
+
+def test_transposed_operand_gives_the_same_product_in_the_other_mode(oracle_mod):
+    # the reason the re-storage exists: NN on (A, B) == NT on (A, B^T) == TN on (A^T, B), bit for bit
+    M, N, K = 9, 14, 11
+    a = synth.normal_bf16(901, (M, K))
+    b = synth.normal_bf16(902, (K, N))
+    ref = oracle_mod.gemm(M, N, K, "NN", a, b)
+    assert np.array_equal(oracle_mod.gemm(M, N, K, "NT", a, oracle_mod.transpose(b)), ref)
+    assert np.array_equal(oracle_mod.gemm(M, N, K, "TN", oracle_mod.transpose(a), b), ref)
