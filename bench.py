@@ -41,12 +41,79 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def bench_transpose(args):
+    """One step = transposing the four weight matrices of the gpt5b layer (what switching their
+    GEMMs to another mode costs once per optimiser step)."""
+    import numpy as np
+    import torch
+
+    from paper_2502_08145_amd import binding as B
+    from paper_2502_08145_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    shapes = [(d_in, d_out) for _, _, d_in, d_out in LAYERS["gpt5b_layer"]]
+    host = [synth.normal_bf16(synth.BASE_SEED + 900 + i, sh, 0.02) for i, sh in enumerate(shapes)]
+    src = [torch.from_numpy(h.view(np.int16)).to(dev).view(torch.bfloat16) for h in host]
+    dst = [torch.empty((c, r), dtype=torch.bfloat16, device=dev) for r, c in shapes]
+    stream = torch.cuda.current_stream()
+    step_bytes = sum(4.0 * r * c for r, c in shapes)          # 2 bytes read + 2 bytes written per element
+
+    def step():
+        for (r, c), s_, d_ in zip(shapes, src, dst):
+            B.axonn_transpose_bf16(r, c, s_, d_, stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in shapes]
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s_i in range(args.steps):
+        for i, ((r, c), s_, d_) in enumerate(zip(shapes, src, dst)):
+            ev[s_i][i][0].record(stream)
+            B.axonn_transpose_bf16(r, c, s_, d_, stream)
+            ev[s_i][i][1].record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    per = [float(np.mean([ev[s_i][i][0].elapsed_time(ev[s_i][i][1]) for s_i in range(args.steps)])) for i in range(len(shapes))]
+    for (r, c), ms in zip(shapes, per):
+        log(f"  transpose [{r:>6d},{c:>6d}]  {ms * 1e3:8.1f} us  {4.0 * r * c / ms / 1e6:7.0f} GB/s")
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    big = max(range(len(shapes)), key=lambda i: per[i])
+    achieved = 4.0 * shapes[big][0] * shapes[big][1] / per[big] / 1e6
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s",
+                "frac": round(achieved / 8000.0, 4), "traffic": None, "kernel": "transpose_tile_kernel",
+                "launches_per_step": 1, "mean_launch_us": round(per[big] * 1e3, 2),
+                "bytes_per_launch": 4.0 * shapes[big][0] * shapes[big][1]}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t0 = time.perf_counter()
+        got = oracle.transpose(host[1])
+        t = time.perf_counter() - t0
+        assert np.array_equal(dst[1].view(torch.int16).cpu().numpy().view(np.uint16), got), "GPU transpose differs from the oracle"
+        cpu = {"value": round(4.0 * shapes[1][0] * shapes[1][1] / t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"the [{shapes[1][0]},{shapes[1][1]}] matrix ({t:.2f} s)"}
+    out = {"metric": "bf16 operand re-storage (transpose) GB/s per GPU", "value": round(value, 1), "unit": "GB/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+           "config": {"workload": "transpose_weights", "matrices": [list(sh) for sh in shapes]},
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="gpt5b_layer", choices=sorted(LAYERS))
+    ap.add_argument("--workload", default="gpt5b_layer", choices=sorted(LAYERS) + ["transpose_weights"],
+                    help="transpose_weights: re-store the four weight matrices of the gpt5b layer for another "
+                         "GEMM mode (HBM-bound side kernel; reports GB/s instead of TFLOP/s)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -58,6 +125,8 @@ def main():
                  "run with --gpus 1")
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: WORLD_SIZE > 1 is not supported: the path is single-GPU")
+    if args.workload == "transpose_weights":
+        return bench_transpose(args)
 
     import numpy as np
     import torch

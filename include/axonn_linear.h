@@ -106,6 +106,16 @@ int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout,
                             const void *X, const void *dY, void *dW,
                             int fp32_accumulate, void *stream);
 
+/* Operand re-storage for another mode (Sec. IV-C: the three modes differ only in how each operand
+ * lies in memory): dst[cols, rows] = transpose of src[rows, cols], bf16 (16-bit) elements, bit
+ * patterns moved unchanged.  DEVICE pointers, row-major, tightly packed, 2-byte aligned, not
+ * overlapping; the caller owns both.  rows, cols >= 0 (nothing to do when either is 0), each below
+ * 2^31.  Shapes that are multiples of 64 with 16-byte aligned pointers take the fast tiled kernel;
+ * others a guarded one, which needs cols <= 262140 (else AXONN_ERR_UNSUPPORTED).  Enqueues on
+ * `stream` and returns.  AXONN_OK, AXONN_ERR_INVALID_ARG, AXONN_ERR_UNSUPPORTED or
+ * AXONN_ERR_LAUNCH; nothing launched on error. */
+int axonn_transpose_bf16(int64_t rows, int64_t cols, const void *src, void *dst, void *stream);
+
 /* ---- support ---------------------------------------------------------------------------- */
 
 /* Human-readable text for a status code; never NULL; static storage. */

@@ -25,7 +25,7 @@ EXPORTS = (
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
     "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
-    "axonn_linear_workspace_bytes", "axonn_linear_set_workspace",
+    "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
 )
 
 _lib = None
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_workspace_bytes.restype = ctypes.c_size_t
         L.axonn_linear_set_workspace.argtypes = [vp, ctypes.c_size_t]
         L.axonn_linear_set_workspace.restype = ci
+        L.axonn_transpose_bf16.argtypes = [i64, i64, vp, vp, vp]
+        L.axonn_transpose_bf16.restype = ci
         L.axonn_linear_init.argtypes = []
         L.axonn_linear_init.restype = ci
         L.axonn_linear_set_split_k.argtypes = [ci]
@@ -200,6 +202,14 @@ def axonn_linear_bwd_data(M, N, K, layout, dY, W, dX, fp32_accumulate=1, stream=
 def axonn_linear_bwd_weight(M, N, K, layout, X, dY, dW, fp32_accumulate=1, stream=None, check=True):
     """dW[M,N] = X^T * dY (Algorithm 1 line 13)."""
     return _call("axonn_linear_bwd_weight", M, N, K, layout, X, dY, dW, fp32_accumulate, stream, check)
+
+
+def axonn_transpose_bf16(rows, cols, src, dst, stream=None, check=True):
+    """dst[cols, rows] = transpose of src[rows, cols] (bf16 tensors or raw device addresses)."""
+    rc = lib().axonn_transpose_bf16(rows, cols, _ptr(src), _ptr(dst), _stream(stream))
+    if check and rc != 0:
+        raise AxonnError(rc, "axonn_transpose_bf16")
+    return rc
 
 
 def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):

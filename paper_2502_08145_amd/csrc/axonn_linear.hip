@@ -9,6 +9,7 @@
 #include <mutex>
 
 #include "gemm_mfma.hpp"
+#include "transpose.hpp"
 
 namespace axonn {
 
@@ -424,6 +425,30 @@ int axonn_linear_mfma_probe(const void* data, size_t data_bytes, int iters, int 
     (void)hipGetLastError();
     hipLaunchKernelGGL(axonn::mfma_probe_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const axonn::u32x4*>(data), static_cast<float*>(sink), iters);
+    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
+}
+
+int axonn_transpose_bf16(int64_t rows, int64_t cols, const void* src, void* dst, void* stream) {
+    constexpr int64_t kMaxDim = (int64_t)1 << 31, kMaxElems = (int64_t)1 << 40;
+    if (rows < 0 || cols < 0 || rows >= kMaxDim || cols >= kMaxDim || rows * cols >= kMaxElems) return AXONN_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return AXONN_OK;
+    const uintptr_t s = reinterpret_cast<uintptr_t>(src), d = reinterpret_cast<uintptr_t>(dst);
+    const uintptr_t bytes = (uintptr_t)rows * (uintptr_t)cols * 2;
+    if (!src || !dst || (s & 1) || (d & 1) || (s < d + bytes && d < s + bytes)) return AXONN_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    if (rows % axonn::TR_TILE == 0 && cols % axonn::TR_TILE == 0 && !(s & 15) && !(d & 15)) {
+        const int64_t tiles = (rows / axonn::TR_TILE) * (cols / axonn::TR_TILE);
+        if (tiles >= kMaxDim) return AXONN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(axonn::transpose_tile_kernel, dim3((unsigned)tiles), dim3(256), 0, st,
+                           static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols,
+                           (int)(cols / axonn::TR_TILE));
+    } else {
+        const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((cols + 3) / 4));
+        if (grid.y > 65535u) return AXONN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(axonn::transpose_naive_kernel, grid, dim3(256), 0, st, static_cast<const uint16_t*>(src),
+                           static_cast<uint16_t*>(dst), rows, cols);
+    }
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
 

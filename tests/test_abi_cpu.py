@@ -118,3 +118,16 @@ def test_workspace_queries_are_host_only():
     assert L.axonn_linear_set_workspace(None, 4096) == B.AXONN_ERR_INVALID_ARG     # size without pointer
     assert L.axonn_linear_set_workspace(0x1010, 1 << 20) == B.AXONN_ERR_INVALID_ARG  # not 256-byte aligned
     assert "scratch" in B.status_string(B.AXONN_ERR_WORKSPACE)
+
+
+def test_transpose_arguments_are_checked_before_any_launch():
+    f = lambda *a: B.axonn_transpose_bf16(*a, stream=0, check=False)
+    bad = B.AXONN_ERR_INVALID_ARG
+    assert f(-1, 8, ALIGNED, ALIGNED + (1 << 20)) == bad
+    assert f(8, -1, ALIGNED, ALIGNED + (1 << 20)) == bad
+    assert f(8, 8, 0, ALIGNED) == bad
+    assert f(8, 8, ALIGNED, 0) == bad
+    assert f(8, 8, ALIGNED + 1, ALIGNED + (1 << 20)) == bad          # odd address
+    assert f(8, 8, ALIGNED, ALIGNED + 64) == bad                     # overlapping buffers
+    assert f(1 << 31, 8, ALIGNED, ALIGNED + (1 << 20)) == bad
+    assert f(0, 8, 0, 0) == B.AXONN_OK and f(8, 0, 0, 0) == B.AXONN_OK

@@ -327,3 +327,39 @@ def test_square_layout_sweep_sampled(oracle_mod, n):
         got = run_gpu("fwd", n, n, n, layout, A, Bm)
         assert np.isfinite(U.bits_to_f64(got)).all()
         U.assert_close(got[ii, jj], ref, f"square {n} {layout}")
+
+
+# ------------------------------------------------------------------ operand re-storage (transpose)
+@pytest.mark.parametrize("shape", [(64, 64), (128, 192), (4096, 1024), (2048, 12288), (1, 7), (65, 130),
+                                   (257, 31), (64, 72), (1000, 8)])
+def test_transpose_matches_oracle_bit_for_bit(oracle_mod, shape):
+    rows, cols = shape
+    # position-coded values (every element differs from its neighbours) XOR seeded noise
+    src = ((np.arange(rows, dtype=np.int64)[:, None] * 251 + np.arange(cols, dtype=np.int64)[None, :] * 7) % 65521)
+    src = (src.astype(np.uint16)) ^ synth.normal_bf16(77, (rows, cols))
+    want = oracle_mod.transpose(src)
+    s = U.to_device(src)
+    d = torch.empty((cols, rows), dtype=torch.bfloat16, device="cuda")
+    d.view(torch.int16).fill_(0x7FC0)
+    B.axonn_transpose_bf16(rows, cols, s, d)
+    torch.cuda.synchronize()
+    got = U.to_host_bits(d)
+    assert np.array_equal(got, want), f"first mismatch at {np.argwhere(got != want)[:1]}"
+    assert np.array_equal(U.to_host_bits(s), src)   # the source is untouched
+
+
+def test_transposed_weight_runs_the_forward_product_in_another_mode(oracle_mod):
+    # Sec. IV-C in one piece: Y = X W computed as NN on (X, W) and as NT on (X, transpose(W))
+    T, d_in, d_out = 512, 768, 1024
+    t = synth.fc_layer_tensors(T, d_in, d_out, synth.BASE_SEED + 700)
+    ref = oracle_mod.gemm(T, d_out, d_in, "NN", t["X"], t["W"])
+    X, W = U.to_device(t["X"]), U.to_device(t["W"])
+    Wt = torch.empty((d_out, d_in), dtype=torch.bfloat16, device="cuda")
+    B.axonn_transpose_bf16(d_in, d_out, W, Wt)
+    y_nn = torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda")
+    y_nt = torch.empty_like(y_nn)
+    B.axonn_linear_fwd(T, d_out, d_in, "NN", X, W, y_nn)
+    B.axonn_linear_fwd(T, d_out, d_in, "NT", X, Wt, y_nt)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_host_bits(y_nn), ref, "fwd NN")
+    U.assert_close(U.to_host_bits(y_nt), ref, "fwd NT on the transposed weight")
