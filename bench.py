@@ -116,6 +116,8 @@ def main():
                          "GEMM mode (HBM-bound side kernel; reports GB/s instead of TFLOP/s)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="store_true",
+                    help="after the timed region, run the mode tuner on every GEMM of the workload and log its table")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="before the timed region, run plain device copies of this many MiB (a kernel of known "
                          "HBM traffic, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -246,6 +248,20 @@ def main():
     torch.cuda.synchronize()
     probe_tflops = cus * 4 * iters * 64 * 32768.0 / (p0.elapsed_time(p1) * 1e-3) / 1e12
     log(f"MFMA-only probe on the same N(0,1) values: {probe_tflops:.1f} TFLOP/s ({cus} CUs, registers only)")
+
+    if args.tune:
+        # the paper's own optimisation (Sec. IV-C): each product timed in NN, NT and TN, with what it
+        # costs to re-store the operands for the other modes
+        log("mode tuner: GEMM us per mode (re-storage of first+second operand in brackets)")
+        names = ["NN", "NT", "TN"]
+        for g in gemms:
+            scratch = torch.empty(((g["M"] * g["K"] * 2 + 255) // 256 * 256 + g["K"] * g["N"] * 2,), dtype=torch.uint8, device=dev)
+            r = B.axonn_linear_tune(g["op"], g["M"], g["N"], g["K"], g["a"], g["b"], g["c"], scratch, stream)
+            cells = "  ".join(f"{names[m]} {r['gemm_us'][m]:7.1f} (+{r['restore_first_us'][m] + r['restore_second_us'][m]:6.1f})"
+                              for m in range(3))
+            log(f"  {g['name']:<22s} natural {g['layout']}: {cells}  best {names[r['best_layout']]}, "
+                f"counting per-call re-storage {names[r['best_layout_all_in']]}")
+            del scratch
 
     # ---- CPU baseline: the oracle as it stands, on a bounded slab of the same GEMMs --------
     cpu = None

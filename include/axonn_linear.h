@@ -116,6 +116,38 @@ int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout,
  * AXONN_ERR_LAUNCH; nothing launched on error. */
 int axonn_transpose_bf16(int64_t rows, int64_t cols, const void *src, void *dst, void *stream);
 
+/* Mode tuner (Sec. IV-C: time each product in the three modes during the first batch and keep the
+ * fastest).  `op` is 0 (fwd), 1 (bwd_data) or 2 (bwd_weight); `first`, `second` are that product's
+ * operands stored the way the method caches them, i.e. in its natural mode (fwd NN, bwd_data NT,
+ * bwd_weight TN), `out` its [M,N] output (overwritten with the product).  For every mode the call
+ * re-stores the operand(s) that mode wants transposed into `scratch` (DEVICE memory, 256-byte
+ * aligned, caller-owned; a mode that needs more than `scratch_bytes` is skipped and reports
+ * gemm_us = -1; M*K*2 rounded up to 256 plus K*N*2 bytes is enough for all), times the re-storage
+ * and the GEMM with events on `stream`, and SYNCHRONISES with the stream.  The result is returned
+ * and remembered under (op, M, N, K):
+ *   gemm_us[m]            mean time of the product in mode m (AXONN_NN, _NT, _TN), microseconds
+ *   restore_first_us[m]   time to re-store the first / second operand for mode m (0 if that mode
+ *   restore_second_us[m]  takes it as cached)
+ *   best_layout           mode with the smallest gemm_us
+ *   best_layout_all_in    mode with the smallest gemm_us + re-storage of the operands that change
+ *                         with every call (all but the weight, i.e. but the second operand of fwd
+ *                         and bwd_data, which changes once per optimiser step)
+ * AXONN_OK, AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
+typedef struct {
+    int best_layout;
+    int best_layout_all_in;
+    float gemm_us[3];
+    float restore_first_us[3];
+    float restore_second_us[3];
+} axonn_tune_result_t;
+int axonn_linear_tune(int op, int64_t M, int64_t N, int64_t K, const void *first, const void *second, void *out,
+                      void *scratch, size_t scratch_bytes, void *stream, axonn_tune_result_t *result);
+/* The remembered result for (op, M, N, K): returns 1 and fills *result, 0 if that product has not
+ * been tuned in this process, AXONN_ERR_INVALID_ARG on a bad argument.  Host only. */
+int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_result_t *result);
+/* Forget all remembered results. */
+void axonn_linear_tune_reset(void);
+
 /* ---- support ---------------------------------------------------------------------------- */
 
 /* Human-readable text for a status code; never NULL; static storage. */

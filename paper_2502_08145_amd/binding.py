@@ -26,9 +26,25 @@ EXPORTS = (
     "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
     "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
+    "axonn_linear_tune", "axonn_linear_tuned", "axonn_linear_tune_reset",
 )
 
 _lib = None
+
+
+class TuneResult(ctypes.Structure):
+    """axonn_tune_result_t"""
+    _fields_ = [("best_layout", ctypes.c_int), ("best_layout_all_in", ctypes.c_int),
+                ("gemm_us", ctypes.c_float * 3), ("restore_first_us", ctypes.c_float * 3),
+                ("restore_second_us", ctypes.c_float * 3)]
+
+    def as_dict(self):
+        return dict(best_layout=self.best_layout, best_layout_all_in=self.best_layout_all_in,
+                    gemm_us=list(self.gemm_us), restore_first_us=list(self.restore_first_us),
+                    restore_second_us=list(self.restore_second_us))
+
+
+OP_INDEX = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}
 
 
 class AxonnError(RuntimeError):
@@ -75,6 +91,13 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_set_workspace.restype = ci
         L.axonn_transpose_bf16.argtypes = [i64, i64, vp, vp, vp]
         L.axonn_transpose_bf16.restype = ci
+        L.axonn_linear_tune.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, ctypes.c_size_t, vp,
+                                        ctypes.POINTER(TuneResult)]
+        L.axonn_linear_tune.restype = ci
+        L.axonn_linear_tuned.argtypes = [ci, i64, i64, i64, ctypes.POINTER(TuneResult)]
+        L.axonn_linear_tuned.restype = ci
+        L.axonn_linear_tune_reset.argtypes = []
+        L.axonn_linear_tune_reset.restype = None
         L.axonn_linear_init.argtypes = []
         L.axonn_linear_init.restype = ci
         L.axonn_linear_set_split_k.argtypes = [ci]
@@ -210,6 +233,31 @@ def axonn_transpose_bf16(rows, cols, src, dst, stream=None, check=True):
     if check and rc != 0:
         raise AxonnError(rc, "axonn_transpose_bf16")
     return rc
+
+
+def axonn_linear_tune(op, M, N, K, first, second, out, scratch, stream=None, check=True):
+    """Time the product `op` ("fwd", "bwd_data", "bwd_weight") in all three modes; returns a dict
+    (see axonn_tune_result_t).  `scratch` is a CUDA tensor for the re-stored operands (or None)."""
+    res = TuneResult()
+    sp, sb = (0, 0) if scratch is None else (scratch.data_ptr(), scratch.numel() * scratch.element_size())
+    rc = lib().axonn_linear_tune(OP_INDEX[op] if isinstance(op, str) else int(op), M, N, K, _ptr(first), _ptr(second),
+                                 _ptr(out), sp, sb, _stream(stream), ctypes.byref(res))
+    if check and rc != 0:
+        raise AxonnError(rc, "axonn_linear_tune")
+    return res.as_dict() if rc == 0 else rc
+
+
+def axonn_linear_tuned(op, M, N, K):
+    """The remembered tuning result for this product, or None."""
+    res = TuneResult()
+    rc = lib().axonn_linear_tuned(OP_INDEX[op] if isinstance(op, str) else int(op), M, N, K, ctypes.byref(res))
+    if rc < 0:
+        raise AxonnError(rc, "axonn_linear_tuned")
+    return res.as_dict() if rc == 1 else None
+
+
+def axonn_linear_tune_reset() -> None:
+    lib().axonn_linear_tune_reset()
 
 
 def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):

@@ -6,7 +6,9 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <map>
 #include <mutex>
+#include <tuple>
 
 #include "gemm_mfma.hpp"
 #include "transpose.hpp"
@@ -306,9 +308,112 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
 
+// ------------------------------------------------------------------------------------------
+// Mode tuner (paper Sec. IV-C): time a product in all three modes once, remember the result.
+// ------------------------------------------------------------------------------------------
+static std::map<std::tuple<int, int64_t, int64_t, int64_t>, axonn_tune_result_t> g_tuned;
+static std::mutex g_tuned_mutex;
+
+static bool first_is_mk(int mode) { return mode != AXONN_TN; }
+static bool second_is_kn(int mode) { return mode != AXONN_NT; }
+
+// Mean time in microseconds of `reps` runs of f() on stream s (after `warm` untimed ones); < 0 on error.
+template <class F>
+static float time_us(hipStream_t s, int warm, int reps, F&& f) {
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return -1.f;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return -1.f;
+    }
+    bool ok = true;
+    for (int i = 0; i < warm && ok; ++i) ok = f() == AXONN_OK;
+    ok = ok && hipEventRecord(e0, s) == hipSuccess;
+    for (int i = 0; i < reps && ok; ++i) ok = f() == AXONN_OK;
+    ok = ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+    float ms = 0.f;
+    ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return ok ? ms * 1000.f / (float)reps : -1.f;
+}
+
 }  // namespace axonn
 
 extern "C" {
+
+int axonn_linear_tune(int op, int64_t M, int64_t N, int64_t K, const void* first, const void* second, void* out,
+                      void* scratch, size_t scratch_bytes, void* stream, axonn_tune_result_t* result) {
+    using namespace axonn;
+    if (op < 0 || op > 2 || !result || M <= 0 || N <= 0 || K <= 0) return AXONN_ERR_INVALID_ARG;
+    const int nat = op;   // fwd: NN, bwd_data: NT, bwd_weight: TN -- the modes the cached buffers give for free
+    int rc = check_args(M, N, K, nat, first, second, out, 1);
+    if (rc != AXONN_OK) return rc;
+    if (scratch_bytes && (!scratch || (reinterpret_cast<uintptr_t>(scratch) & 255))) return AXONN_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t first_bytes = (((size_t)M * K * 2) + 255) & ~(size_t)255, second_bytes = (size_t)K * N * 2;
+    axonn_tune_result_t r;
+    r.best_layout = r.best_layout_all_in = nat;
+    float best = -1.f, best_all = -1.f;
+    for (int m = 0; m < 3; ++m) {
+        r.gemm_us[m] = -1.f;
+        r.restore_first_us[m] = r.restore_second_us[m] = 0.f;
+        const bool tf = first_is_mk(m) != first_is_mk(nat), ts = second_is_kn(m) != second_is_kn(nat);
+        const size_t need = (tf ? first_bytes : 0) + (ts ? second_bytes : 0);
+        if (need > scratch_bytes) continue;   // this mode cannot be tried
+        const void* a = first;
+        const void* b = second;
+        char* free_ptr = static_cast<char*>(scratch);
+        if (tf) {
+            const int64_t rows = first_is_mk(nat) ? M : K, cols = first_is_mk(nat) ? K : M;
+            void* dst = free_ptr;
+            free_ptr += first_bytes;
+            r.restore_first_us[m] = time_us(s, 1, 3, [&] { return axonn_transpose_bf16(rows, cols, first, dst, stream); });
+            if (r.restore_first_us[m] < 0.f) return AXONN_ERR_LAUNCH;
+            a = dst;
+        }
+        if (ts) {
+            const int64_t rows = second_is_kn(nat) ? K : N, cols = second_is_kn(nat) ? N : K;
+            void* dst = free_ptr;
+            r.restore_second_us[m] = time_us(s, 1, 3, [&] { return axonn_transpose_bf16(rows, cols, second, dst, stream); });
+            if (r.restore_second_us[m] < 0.f) return AXONN_ERR_LAUNCH;
+            b = dst;
+        }
+        r.gemm_us[m] = time_us(s, 2, 5, [&] { return launch(M, N, K, m, a, b, out, 1, stream); });
+        if (r.gemm_us[m] < 0.f) return AXONN_ERR_LAUNCH;
+        // the weight (second operand of fwd and bwd_data) changes once per optimiser step, the other
+        // operands with every call: only their re-storage is charged to the call
+        const float all_in = r.gemm_us[m] + r.restore_first_us[m] + (op == 2 ? r.restore_second_us[m] : 0.f);
+        if (best < 0.f || r.gemm_us[m] < best) {
+            best = r.gemm_us[m];
+            r.best_layout = m;
+        }
+        if (best_all < 0.f || all_in < best_all) {
+            best_all = all_in;
+            r.best_layout_all_in = m;
+        }
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_tuned_mutex);
+        g_tuned[std::make_tuple(op, M, N, K)] = r;
+    }
+    *result = r;
+    return AXONN_OK;
+}
+
+int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_result_t* result) {
+    if (op < 0 || op > 2 || !result) return AXONN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(axonn::g_tuned_mutex);
+    auto it = axonn::g_tuned.find(std::make_tuple(op, M, N, K));
+    if (it == axonn::g_tuned.end()) return 0;
+    *result = it->second;
+    return 1;
+}
+
+void axonn_linear_tune_reset(void) {
+    std::lock_guard<std::mutex> lock(axonn::g_tuned_mutex);
+    axonn::g_tuned.clear();
+}
 
 int axonn_linear_fwd(int64_t M, int64_t N, int64_t K, int layout, const void* X, const void* W, void* Y,
                      int fp32_accumulate, void* stream) {

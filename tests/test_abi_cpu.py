@@ -131,3 +131,20 @@ def test_transpose_arguments_are_checked_before_any_launch():
     assert f(8, 8, ALIGNED, ALIGNED + 64) == bad                     # overlapping buffers
     assert f(1 << 31, 8, ALIGNED, ALIGNED + (1 << 20)) == bad
     assert f(0, 8, 0, 0) == B.AXONN_OK and f(8, 0, 0, 0) == B.AXONN_OK
+
+
+def test_tuner_host_side():
+    B.axonn_linear_tune_reset()
+    assert B.axonn_linear_tuned("fwd", 256, 256, 256) is None
+    with pytest.raises(B.AxonnError):
+        B.axonn_linear_tuned(3, 256, 256, 256)
+    # bad arguments are refused before anything touches a GPU
+    res = B.TuneResult()
+    L = B.lib()
+    import ctypes
+    bad = B.AXONN_ERR_INVALID_ARG
+    assert L.axonn_linear_tune(5, 256, 256, 256, ALIGNED, ALIGNED, ALIGNED, None, 0, None, ctypes.byref(res)) == bad
+    assert L.axonn_linear_tune(0, 0, 256, 256, ALIGNED, ALIGNED, ALIGNED, None, 0, None, ctypes.byref(res)) == bad
+    assert L.axonn_linear_tune(0, 256, 256, 256, 0, ALIGNED, ALIGNED, None, 0, None, ctypes.byref(res)) == bad
+    assert L.axonn_linear_tune(0, 256, 256, 256, ALIGNED, ALIGNED, ALIGNED, ALIGNED + 16, 1 << 20, None, ctypes.byref(res)) == bad
+    assert L.axonn_linear_tune(0, 256, 256, 256, ALIGNED, ALIGNED, ALIGNED, None, 0, None, None) == bad

@@ -363,3 +363,36 @@ def test_transposed_weight_runs_the_forward_product_in_another_mode(oracle_mod):
     torch.cuda.synchronize()
     U.assert_close(U.to_host_bits(y_nn), ref, "fwd NN")
     U.assert_close(U.to_host_bits(y_nt), ref, "fwd NT on the transposed weight")
+
+
+# ------------------------------------------------------------------ mode tuner (Sec. IV-C)
+@pytest.mark.parametrize("op", ["fwd", "bwd_data", "bwd_weight"])
+def test_tuner_times_all_modes_and_leaves_the_right_product(oracle_mod, op):
+    T, d_in, d_out = 512, 768, 1024
+    t = synth.fc_layer_tensors(T, d_in, d_out, synth.BASE_SEED + 800)
+    g = next(x for x in synth.fc_layer_gemms(T, d_in, d_out, "fc") if x["op"] == op)
+    M, N, K, nat = g["M"], g["N"], g["K"], g["layout"]
+    A, Bm = synth.operands_for(op, nat, t)
+    ref = oracle_mod.gemm(M, N, K, nat, A, Bm)
+    a, b = U.to_device(A), U.to_device(Bm)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    c.view(torch.int16).fill_(0x7FC0)
+    scratch = torch.empty(((M * K * 2 + 255) // 256 * 256 + K * N * 2,), dtype=torch.uint8, device="cuda")
+    B.axonn_linear_tune_reset()
+    res = B.axonn_linear_tune(op, M, N, K, a, b, c, scratch)
+    torch.cuda.synchronize()
+    assert all(us > 0 for us in res["gemm_us"]), res
+    assert res["best_layout"] == int(np.argmin(res["gemm_us"]))
+    nat_i = B.LAYOUTS[nat]
+    assert res["restore_first_us"][nat_i] == 0 and res["restore_second_us"][nat_i] == 0
+    for m in range(3):   # a mode pays for exactly the operands it wants stored the other way
+        assert (res["restore_first_us"][m] > 0) == ((m != 2) != (nat_i != 2))
+        assert (res["restore_second_us"][m] > 0) == ((m != 1) != (nat_i != 1))
+    # the last mode timed (TN) ran on re-stored operands unless TN is the natural mode: its output
+    # is the product all the same
+    U.assert_close(U.to_host_bits(c), ref, f"tuner output {op}")
+    assert B.axonn_linear_tuned(op, M, N, K) == res
+    # without scratch only the natural mode can be tried, and it wins
+    B.axonn_linear_tune_reset()
+    res0 = B.axonn_linear_tune(op, M, N, K, a, b, c, None)
+    assert res0["best_layout"] == nat_i and sorted(us > 0 for us in res0["gemm_us"]) == [False, False, True]
