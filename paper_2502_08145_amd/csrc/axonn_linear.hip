@@ -116,6 +116,9 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT("mfma_256x256_sk4", 256, 256, 2, 2, 4, 1),
     AXONN_TILE_VARIANT("mfma_256x256_w8_sk2", 256, 256, 2, 4, 2, 5),
     AXONN_TILE_VARIANT("mfma_256x256_w8_sk4", 256, 256, 2, 4, 4, 5),
+    // ... or per 128x128 tile (small shard shapes)
+    AXONN_TILE_VARIANT("mfma_128x128_sk2", 128, 128, 2, 2, 2, 4),
+    AXONN_TILE_VARIANT("mfma_128x128_sk4", 128, 128, 2, 2, 4, 4),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -126,11 +129,12 @@ constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 constexpr int kScratchSlots = 256;                          // the most any variant is allowed to need
 constexpr size_t kSlotBytes = 256 * 256 * sizeof(float);
 constexpr size_t kFlagBytes = 4096;                         // 1023 flags + the counter
+constexpr int64_t kMaxFlags = kFlagBytes / sizeof(uint32_t) - 1;
 constexpr int kMaxDevices = 64;
 struct Scratch {
     float* partials = nullptr;
     uint32_t* flags = nullptr;
-    int slots = 0;
+    size_t partial_bytes = 0;       // capacity behind `partials`
     void* owned = nullptr;          // the library's own allocation, if it made one
     uint32_t* timeouts() const { return flags + kFlagBytes / sizeof(uint32_t) - 1; }
 };
@@ -145,17 +149,15 @@ static bool adopt(Scratch& sc, void* p, size_t bytes) {
         (void)hipGetLastError();
         return false;
     }
-    size_t slots = (bytes - kFlagBytes) / kSlotBytes;
-    if (slots > (size_t)kScratchSlots) slots = kScratchSlots;
     sc.flags = static_cast<uint32_t*>(p);
     sc.partials = reinterpret_cast<float*>(static_cast<char*>(p) + kFlagBytes);
-    sc.slots = (int)slots;
+    sc.partial_bytes = bytes - kFlagBytes;
     return true;
 }
 
 // The current device's scratch area (by value: a later set_workspace does not disturb a launch being
-// prepared), with at least `slots_needed` slots; .partials == nullptr if that cannot be had.
-static Scratch get_scratch(int slots_needed) {
+// prepared), with room for `bytes_needed` bytes of partial tiles; .partials == nullptr if that cannot be had.
+static Scratch get_scratch(size_t bytes_needed) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Scratch{};
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
@@ -173,7 +175,7 @@ static Scratch get_scratch(int slots_needed) {
         }
         sc.owned = p;
     }
-    return sc.slots >= slots_needed ? sc : Scratch{};
+    return sc.partial_bytes >= bytes_needed ? sc : Scratch{};
 }
 
 static std::atomic<int> g_forced{-1};
@@ -185,7 +187,10 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
     if (M % var.bm != 0 || N % var.bn != 0 || K % (KB * var.splits) != 0 || K / var.splits < var.min_k) return false;
-    return var.splits == 1 || (M / var.bm) * (N / var.bn) * (var.splits - 1) <= kScratchSlots;
+    if (var.splits == 1) return true;
+    // scratch: one flag and one fp32 tile per (tile, extra K range)
+    const int64_t slots = (M / var.bm) * (N / var.bn) * (var.splits - 1);
+    return slots <= kMaxFlags && slots * var.bm * var.bn * (int64_t)sizeof(float) <= (int64_t)(kScratchSlots * kSlotBytes);
 }
 
 // Tile-shape choice.  MI355X has 256 compute units; a partly filled last round of tiles costs a
@@ -205,7 +210,7 @@ static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allo
         /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70},
         /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95},
     };
-    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0;
+    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0, kFixedKSplitSmall = 384.0;
     int best = 0;
     double best_t = 0;
     for (int v = 1; v < kNumVariants; ++v) {
@@ -217,10 +222,12 @@ static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allo
         // a fraction f of the CUs runs faster than a full one (the busy CUs get the idle ones'
         // power and bandwidth): measured about 0.5 + 0.5 f of a full round.
         const int64_t full = wgs / 256, rest = wgs % 256;
-        if (var.splits > 1 && full + (rest ? 1 : 0) > 1) continue;   // readers and writers of a tile run side by side
+        // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
+        if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) continue;
         const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
         const double k_cost = (double)(K / var.splits) +
-                              (var.splits == 1 ? kFixedK : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
+                              (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedKSplitSmall
+                               : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
         const double t = rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
         if (best == 0 || t < best_t) {
             best = v;
@@ -263,16 +270,16 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
 
     int v = g_forced.load(std::memory_order_relaxed);
     Scratch scratch;
-    auto slots_needed = [&](int variant) {
+    auto bytes_needed = [&](int variant) {
         const Variant& x = g_variants[variant];
-        return (int)((M / x.bm) * (N / x.bn) * (x.splits - 1));
+        return (size_t)((M / x.bm) * (N / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
     };
     if (v >= 0) {
         if (!variant_supports(v, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch(slots_needed(v))).partials) return AXONN_ERR_WORKSPACE;
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch(bytes_needed(v))).partials) return AXONN_ERR_WORKSPACE;
     } else {
         v = select_variant(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch(slots_needed(v))).partials)
+        if (g_variants[v].splits > 1 && !(scratch = get_scratch(bytes_needed(v))).partials)
             v = select_variant(M, N, K, layout, false);
     }
     const Variant& var = g_variants[v];
@@ -460,7 +467,7 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
 
 int axonn_linear_init(void) {
     std::call_once(axonn::g_attr_once, axonn::raise_lds_limits);
-    return axonn::get_scratch(1).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
+    return axonn::get_scratch(axonn::kSlotBytes).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
 }
 
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout) {
@@ -468,7 +475,7 @@ size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout)
     const int v = axonn::select_variant(M, N, K, layout, true);
     const axonn::Variant& var = axonn::g_variants[v];
     if (var.splits == 1) return 0;
-    return axonn::kFlagBytes + (size_t)((M / var.bm) * (N / var.bn) * (var.splits - 1)) * axonn::kSlotBytes;
+    return axonn::kFlagBytes + (size_t)((M / var.bm) * (N / var.bn) * (var.splits - 1)) * var.bm * var.bn * sizeof(float);
 }
 
 int axonn_linear_set_workspace(void* dev_ptr, size_t bytes) {

@@ -1,0 +1,123 @@
+"""Shape sweeps of the FC-layer GEMMs on one MI355X (timing only; parity is the tests' job).
+
+    python -m paper_2502_08145_amd.sweeps peak_curve [--max 65536]
+    python -m paper_2502_08145_amd.sweeps model_zoo [--tokens 2048]
+
+peak_curve   square bf16 GEMMs 1024 ... 65536 in the three modes, the protocol of the paper's
+             single-GPU GEMM benchmark (Sec. V-C: repeated runs, mean of the last three quarters),
+             with the repetition count scaled down so that one size takes a few seconds.
+model_zoo    the shard shapes of the paper's model table (Sec. V-A, Table II: hidden 4096 ... 16384,
+             FFN 4h, fused QKV 3h) under every split of a weight's two dimensions by 1, 2, 4 or 8
+             (Sec. IV-A: a weight is sharded over two of the grid's dimensions), forward,
+             backward-data and backward-weight in their natural modes.
+
+Operands are N(0,1) (activations, gradients) and N(0, 0.02^2) (weights) drawn on the device with a
+fixed seed: host generation of 65536^2 matrices would take minutes.  Output: one text line per
+GEMM / per hidden size on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import torch
+
+from . import binding as B
+
+PEAK = 2516.6
+
+
+def time_gemm(op, M, N, K, layout, a, b, c, reps, warm=3):
+    stream = torch.cuda.current_stream()
+    for _ in range(warm):
+        B.OPS[op](M, N, K, layout, a, b, c, 1, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ev[0].record(stream)
+    for i in range(reps):
+        B.OPS[op](M, N, K, layout, a, b, c, 1, stream)
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    t = [ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]
+    tail = t[len(t) // 4:]            # mean of the last three quarters
+    return sum(tail) / len(tail)      # ms
+
+
+def randn_bf16(shape, sigma, gen):
+    return (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * sigma).to(torch.bfloat16)
+
+
+def peak_curve(args):
+    gen = torch.Generator(device="cuda").manual_seed(250208145)
+    n = 1024
+    print(f"{'n':>6s} {'mode':>4s} {'variant':<22s} {'reps':>4s} {'ms':>10s} {'TFLOP/s':>9s} {'% peak':>7s}")
+    while n <= args.max:
+        a = randn_bf16((n, n), 1.0, gen)
+        b = randn_bf16((n, n), 1.0, gen)
+        c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+        for layout in ("NN", "NT", "TN"):
+            est = 2.0 * n ** 3 / 1.0e15 * 1e3            # ms at 1 PFLOP/s
+            reps = int(max(4, min(100, 2000.0 / max(est, 1e-3))))
+            ms = time_gemm("fwd", n, n, n, layout, a, b, c, reps)
+            tf = 2.0 * n ** 3 / ms / 1e9
+            v = B.variant_name(B.select_variant(n, n, n, layout))
+            print(f"{n:6d} {layout:>4s} {v:<22s} {reps:4d} {ms:10.4f} {tf:9.1f} {tf / PEAK * 100:6.1f}%", flush=True)
+        del a, b, c
+        n *= 2
+
+
+def model_zoo(args):
+    gen = torch.Generator(device="cuda").manual_seed(250208146)
+    T = args.tokens
+    splits = (1, 2, 4, 8)
+    print(f"tokens per GPU {T}; per hidden size: all 16 splits x 4 layers x 3 products")
+    print(f"{'hidden':>6s} {'GEMMs':>5s} {'guarded':>7s} {'min':>8s} {'median':>8s} {'max':>8s} {'aggregate':>9s}  slowest shape")
+    for h in (4096, 5120, 7168, 9216, 12288, 16384):
+        layers = [("qkv", h, 3 * h), ("attn_out", h, h), ("fc1", h, 4 * h), ("fc2", 4 * h, h)]
+        rates, flops_sum, ms_sum, guarded, worst = [], 0.0, 0.0, 0, None
+        for name, d_in, d_out in layers:
+            for ga in splits:
+                for gb in splits:
+                    di, do = d_in // ga, d_out // gb
+                    X = randn_bf16((T, di), 1.0, gen)
+                    W = randn_bf16((di, do), 0.02, gen)
+                    dY = randn_bf16((T, do), 1.0, gen)
+                    for op, lay, M, N, K, p, q in (("fwd", "NN", T, do, di, X, W), ("bwd_data", "NT", T, di, do, dY, W),
+                                                   ("bwd_weight", "TN", di, do, T, X, dY)):
+                        c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+                        v = B.select_variant(M, N, K, lay)
+                        guarded += v == 0
+                        ms = time_gemm(op, M, N, K, lay, p, q, c, 12 if v else 3, warm=2)
+                        fl = 2.0 * M * N * K
+                        tf = fl / ms / 1e9
+                        rates.append(tf)
+                        flops_sum += fl
+                        ms_sum += ms
+                        if worst is None or tf < worst[0]:
+                            worst = (tf, f"{name}.{op} {lay} M={M} N={N} K={K} {B.variant_name(v)}")
+                        if args.verbose:
+                            print(f"   {h} {name}.{op} {lay} M={M} N={N} K={K} {B.variant_name(v)} {ms * 1e3:.1f} us {tf:.0f}", flush=True)
+                    del X, W, dY
+        rates.sort()
+        print(f"{h:6d} {len(rates):5d} {guarded:7d} {rates[0]:8.1f} {rates[len(rates) // 2]:8.1f} {rates[-1]:8.1f} "
+              f"{flops_sum / ms_sum / 1e9:9.1f}  {worst[1]} ({worst[0]:.0f} TFLOP/s)", flush=True)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    p = sub.add_parser("peak_curve")
+    p.add_argument("--max", type=int, default=65536)
+    z = sub.add_parser("model_zoo")
+    z.add_argument("--tokens", type=int, default=2048)
+    z.add_argument("--verbose", action="store_true")
+    args = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        sys.exit("sweeps: no GPU visible")
+    B.lib()
+    B.axonn_linear_init()
+    torch.cuda.set_device(0)
+    {"peak_curve": peak_curve, "model_zoo": model_zoo}[args.cmd](args)
+
+
+if __name__ == "__main__":
+    main()

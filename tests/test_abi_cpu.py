@@ -85,8 +85,11 @@ def test_variant_table_and_selection():
             assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
             splits = {"sk2": 2, "sk4": 4}.get(names[v].rsplit("_", 1)[-1], 1)
             assert B.variant_supports(v, 256, 256, 160 * splits, lay)   # per K range
-            # split-K keeps (splits - 1) partial tiles per output tile in a scratch area of 256 tiles
-            assert B.variant_supports(v, 4096, 4096, 4096, lay) == (splits <= 2)
+            # split-K keeps (splits - 1) fp32 partial tiles per output tile in a 64 MiB scratch area
+            # with 1023 flags
+            bm, bn = (int(x) for x in names[v].split("_")[1].split("x"))
+            slots = (4096 // bm) * (4096 // bn) * (splits - 1)
+            assert B.variant_supports(v, 4096, 4096, 4096, lay) == (slots <= 1023 and slots * bm * bn * 4 <= 64 << 20)
         # ragged or degenerate shapes go to the guarded kernel, large ones to an MFMA kernel
         assert B.select_variant(100, 200, 300, lay) == 0
         assert B.select_variant(256, 256, 0, lay) == 0
