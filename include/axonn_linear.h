@@ -148,6 +148,43 @@ int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_resul
 /* Forget all remembered results. */
 void axonn_linear_tune_reset(void);
 
+/* ---- communication performance model (Sec. V-A, Eq. 1-7); host only, no GPU is touched -------- */
+
+/* One FC layer: an m x k input batch times a k x n weight (global sizes, before any sharding);
+ * transposed != 0 for the layers whose weight is stored 'transposed', for which the X and Y process
+ * groups trade places. */
+typedef struct {
+    int64_t m, k, n;
+    int transposed;
+} axonn_comm_layer_t;
+
+/* A 4D grid and the modelled communication time of one pass over the layers. */
+typedef struct {
+    int gx, gy, gz, gdata;
+    double seconds;
+} axonn_comm_grid_t;
+
+/* Bandwidth (bytes/s) each of the four process groups of grid[4] = {G_x, G_y, G_z, G_data} sees,
+ * hierarchy X innermost.  A group that fits in a node of g_node GPUs reads the profiled table
+ * intra_bw[inner * (g_node + 1) + size] (inner = product of the inner group sizes, size = own size;
+ * (g_node + 1)^2 doubles, entries with inner * size <= g_node and size >= 2 are used); a group
+ * spanning nodes gets beta_inter / min(g_node, inner) (Eq. 7).  A group of one GPU gets +infinity.
+ * AXONN_OK, or AXONN_ERR_INVALID_ARG (bad sizes, or a needed table entry is missing or <= 0). */
+int axonn_comm_group_bandwidths(const int *grid, int g_node, double beta_inter, const double *intra_bw,
+                                double *beta_out);
+
+/* Eq. 1-6 for one layer: terms_out[6] = {all-gather_z, reduce-scatter_z, all-reduce_y, all-reduce_x,
+ * all-reduce_data, their sum} in seconds, for beta[4] = bandwidths of the X, Y, Z, data groups. */
+int axonn_comm_layer_time(const axonn_comm_layer_t *layer, const int *grid, const double *beta,
+                          double bytes_per_element, double *terms_out);
+
+/* Every ordered factorisation G_x * G_y * G_z * G_data = g_total, ranked by the summed time over the
+ * layers (ties: smaller G_x, then G_y, G_z first).  Writes the best min(max_out, count) grids to
+ * `out` and returns the count of all grids, or a negative error code. */
+int64_t axonn_comm_rank_grids(int64_t g_total, const axonn_comm_layer_t *layers, int n_layers, int g_node,
+                              double beta_inter, const double *intra_bw, double bytes_per_element,
+                              axonn_comm_grid_t *out, int64_t max_out);
+
 /* ---- support ---------------------------------------------------------------------------- */
 
 /* Human-readable text for a status code; never NULL; static storage. */

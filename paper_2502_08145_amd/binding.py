@@ -27,6 +27,7 @@ EXPORTS = (
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
     "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
     "axonn_linear_tune", "axonn_linear_tuned", "axonn_linear_tune_reset",
+    "axonn_comm_group_bandwidths", "axonn_comm_layer_time", "axonn_comm_rank_grids",
 )
 
 _lib = None
@@ -45,6 +46,17 @@ class TuneResult(ctypes.Structure):
 
 
 OP_INDEX = {"fwd": 0, "bwd_data": 1, "bwd_weight": 2}
+
+
+class CommLayer(ctypes.Structure):
+    """axonn_comm_layer_t"""
+    _fields_ = [("m", ctypes.c_int64), ("k", ctypes.c_int64), ("n", ctypes.c_int64), ("transposed", ctypes.c_int)]
+
+
+class CommGrid(ctypes.Structure):
+    """axonn_comm_grid_t"""
+    _fields_ = [("gx", ctypes.c_int), ("gy", ctypes.c_int), ("gz", ctypes.c_int), ("gdata", ctypes.c_int),
+                ("seconds", ctypes.c_double)]
 
 
 class AxonnError(RuntimeError):
@@ -98,6 +110,14 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_tuned.restype = ci
         L.axonn_linear_tune_reset.argtypes = []
         L.axonn_linear_tune_reset.restype = None
+        dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)
+        L.axonn_comm_group_bandwidths.argtypes = [ip, ci, ctypes.c_double, dp, dp]
+        L.axonn_comm_group_bandwidths.restype = ci
+        L.axonn_comm_layer_time.argtypes = [ctypes.POINTER(CommLayer), ip, dp, ctypes.c_double, dp]
+        L.axonn_comm_layer_time.restype = ci
+        L.axonn_comm_rank_grids.argtypes = [i64, ctypes.POINTER(CommLayer), ci, ci, ctypes.c_double, dp,
+                                            ctypes.c_double, ctypes.POINTER(CommGrid), i64]
+        L.axonn_comm_rank_grids.restype = i64
         L.axonn_linear_init.argtypes = []
         L.axonn_linear_init.restype = ci
         L.axonn_linear_set_split_k.argtypes = [ci]
@@ -258,6 +278,52 @@ def axonn_linear_tuned(op, M, N, K):
 
 def axonn_linear_tune_reset() -> None:
     lib().axonn_linear_tune_reset()
+
+
+def _intra_table(g_node, intra_db):
+    """{(inner, size): bytes/s} -> the flat (g_node + 1)^2 table the C ABI takes."""
+    tab = (ctypes.c_double * ((g_node + 1) * (g_node + 1)))()
+    for (inner, size), bw in (intra_db or {}).items():
+        if inner <= g_node and size <= g_node:
+            tab[inner * (g_node + 1) + size] = float(bw)
+    return tab
+
+
+def axonn_comm_group_bandwidths(grid, g_node, beta_inter, intra_db):
+    g = (ctypes.c_int * 4)(*grid)
+    out = (ctypes.c_double * 4)()
+    rc = lib().axonn_comm_group_bandwidths(g, g_node, float(beta_inter), _intra_table(g_node, intra_db), out)
+    if rc != 0:
+        raise AxonnError(rc, "axonn_comm_group_bandwidths")
+    return tuple(out)
+
+
+def axonn_comm_layer_time(m, k, n, grid, beta, bytes_per_element=2.0, transposed=False):
+    layer = CommLayer(m, k, n, 1 if transposed else 0)
+    g = (ctypes.c_int * 4)(*grid)
+    b = (ctypes.c_double * 4)(*[float(x) for x in beta])
+    out = (ctypes.c_double * 6)()
+    rc = lib().axonn_comm_layer_time(ctypes.byref(layer), g, b, float(bytes_per_element), out)
+    if rc != 0:
+        raise AxonnError(rc, "axonn_comm_layer_time")
+    return dict(zip(("ag_z", "rs_z", "ar_y", "ar_x", "ar_data", "total"), out))
+
+
+def axonn_comm_rank_grids(g_total, layers, g_node, beta_inter, intra_db, bytes_per_element=2.0, top=None):
+    """[(seconds, (G_x, G_y, G_z, G_data))], best first; layers = [(m, k, n, transposed)]."""
+    arr = (CommLayer * max(1, len(layers)))(*[CommLayer(m, k, n, 1 if t else 0) for m, k, n, t in layers])
+    tab = _intra_table(g_node, intra_db)
+    count = lib().axonn_comm_rank_grids(g_total, arr, len(layers), g_node, float(beta_inter), tab,
+                                        float(bytes_per_element), None, 0)
+    if count < 0:
+        raise AxonnError(int(count), "axonn_comm_rank_grids")
+    n = count if top is None else min(top, count)
+    out = (CommGrid * max(1, n))()
+    rc = lib().axonn_comm_rank_grids(g_total, arr, len(layers), g_node, float(beta_inter), tab,
+                                     float(bytes_per_element), out, n)
+    if rc < 0:
+        raise AxonnError(int(rc), "axonn_comm_rank_grids")
+    return [(out[i].seconds, (out[i].gx, out[i].gy, out[i].gz, out[i].gdata)) for i in range(n)]
 
 
 def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):

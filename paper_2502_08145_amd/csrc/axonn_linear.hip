@@ -11,6 +11,7 @@
 #include <tuple>
 
 #include "gemm_mfma.hpp"
+#include "comm_model.hpp"
 #include "transpose.hpp"
 
 namespace axonn {
@@ -562,6 +563,73 @@ int axonn_transpose_bf16(int64_t rows, int64_t cols, const void* src, void* dst,
                            static_cast<uint16_t*>(dst), rows, cols);
     }
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
+}
+
+static bool comm_args_ok(const int* grid, int g_node, double beta_inter, double bytes_per_element) {
+    if (!grid || g_node < 1 || !(beta_inter > 0.0) || !(bytes_per_element > 0.0)) return false;
+    for (int i = 0; i < 4; ++i)
+        if (grid[i] < 1) return false;
+    return true;
+}
+
+int axonn_comm_group_bandwidths(const int* grid, int g_node, double beta_inter, const double* intra_bw, double* beta_out) {
+    if (!comm_args_ok(grid, g_node, beta_inter, 1.0) || !beta_out) return AXONN_ERR_INVALID_ARG;
+    return axonn::comm_group_bandwidths(grid, g_node, beta_inter, intra_bw, beta_out) ? AXONN_OK : AXONN_ERR_INVALID_ARG;
+}
+
+int axonn_comm_layer_time(const axonn_comm_layer_t* layer, const int* grid, const double* beta, double bytes_per_element,
+                          double* terms_out) {
+    if (!layer || !beta || !terms_out || !comm_args_ok(grid, 1, 1.0, bytes_per_element)) return AXONN_ERR_INVALID_ARG;
+    if (layer->m < 0 || layer->k < 0 || layer->n < 0) return AXONN_ERR_INVALID_ARG;
+    for (int i = 0; i < 4; ++i)
+        if (grid[i] > 1 && !(beta[i] > 0.0)) return AXONN_ERR_INVALID_ARG;
+    axonn::comm_layer_terms(*layer, grid, beta, bytes_per_element, terms_out);
+    return AXONN_OK;
+}
+
+int64_t axonn_comm_rank_grids(int64_t g_total, const axonn_comm_layer_t* layers, int n_layers, int g_node,
+                              double beta_inter, const double* intra_bw, double bytes_per_element,
+                              axonn_comm_grid_t* out, int64_t max_out) {
+    const int one[4] = {1, 1, 1, 1};
+    if (g_total < 1 || g_total > ((int64_t)1 << 30) || n_layers < 0 || (n_layers > 0 && !layers) || max_out < 0 ||
+        (max_out > 0 && !out) || !comm_args_ok(one, g_node, beta_inter, bytes_per_element))
+        return AXONN_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (layers[l].m < 0 || layers[l].k < 0 || layers[l].n < 0) return AXONN_ERR_INVALID_ARG;
+    std::vector<int64_t> divs;
+    for (int64_t d = 1; d * d <= g_total; ++d)
+        if (g_total % d == 0) {
+            divs.push_back(d);
+            if (d != g_total / d) divs.push_back(g_total / d);
+        }
+    std::sort(divs.begin(), divs.end());
+    std::vector<axonn_comm_grid_t> rows;
+    for (int64_t gx : divs)
+        for (int64_t gy : divs) {
+            if ((g_total / gx) % gy) continue;
+            const int64_t r2 = g_total / gx / gy;
+            for (int64_t gz : divs) {
+                if (r2 % gz) continue;
+                const int grid[4] = {(int)gx, (int)gy, (int)gz, (int)(r2 / gz)};
+                double beta[4], terms[6], total = 0.0;
+                if (!axonn::comm_group_bandwidths(grid, g_node, beta_inter, intra_bw, beta)) return AXONN_ERR_INVALID_ARG;
+                for (int l = 0; l < n_layers; ++l) {
+                    axonn::comm_layer_terms(layers[l], grid, beta, bytes_per_element, terms);
+                    total += terms[5];
+                }
+                rows.push_back(axonn_comm_grid_t{grid[0], grid[1], grid[2], grid[3], total});
+            }
+        }
+    std::sort(rows.begin(), rows.end(), [](const axonn_comm_grid_t& a, const axonn_comm_grid_t& b) {
+        if (a.seconds != b.seconds) return a.seconds < b.seconds;
+        if (a.gx != b.gx) return a.gx < b.gx;
+        if (a.gy != b.gy) return a.gy < b.gy;
+        if (a.gz != b.gz) return a.gz < b.gz;
+        return a.gdata < b.gdata;
+    });
+    const int64_t n_out = std::min<int64_t>(max_out, (int64_t)rows.size());
+    for (int64_t i = 0; i < n_out; ++i) out[i] = rows[i];
+    return (int64_t)rows.size();
 }
 
 int axonn_linear_force_variant(int variant) {
