@@ -11,6 +11,7 @@
 #include <tuple>
 
 #include "gemm_mfma.hpp"
+#include "gemm_mfma16.hpp"
 #include "comm_model.hpp"
 #include "transpose.hpp"
 
@@ -88,6 +89,7 @@ typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, 
 struct Variant {
     const char* name;
     int bm, bn, threads, lds_bytes, min_k;  // bm == 0: the naive kernel; min_k per K range
+    int kstep;                       // K (per range) must be a multiple of this
     int splits;                      // K ranges per tile (1: no split-K)
     int base;                        // index of the variant whose measured efficiency applies
     tile_kernel_t fn[3];             // per layout
@@ -96,15 +98,26 @@ struct Variant {
 #define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN, SPLITS, BASE)                                       \
     {                                                                                                \
         NAME, BM, BN, TileCfg<BM, BN, WM, WN>::NT, TileCfg<BM, BN, WM, WN>::LDS_BYTES,               \
-            TileCfg<BM, BN, WM, WN>::MIN_K, SPLITS, BASE, {                                          \
+            TileCfg<BM, BN, WM, WN>::MIN_K, KB, SPLITS, BASE, {                                      \
             gemm_tile_kernel<BM, BN, WM, WN, true, false, (SPLITS > 1)>,                             \
                 gemm_tile_kernel<BM, BN, WM, WN, true, true, (SPLITS > 1)>,                          \
                 gemm_tile_kernel<BM, BN, WM, WN, false, false, (SPLITS > 1)>                         \
         }                                                                                            \
     }
 
+// the same on 16x16x32 MFMAs (two K-steps per loop iteration: K a multiple of 64)
+#define AXONN_TILE_VARIANT16(NAME, BM, BN, WM, WN, SPLITS, BASE)                                     \
+    {                                                                                                \
+        NAME, BM, BN, TileCfg16<BM, BN, WM, WN>::NT, TileCfg16<BM, BN, WM, WN>::LDS_BYTES,           \
+            TileCfg16<BM, BN, WM, WN>::MIN_K, 2 * KB, SPLITS, BASE, {                                \
+            gemm_tile_kernel16<BM, BN, WM, WN, true, false, (SPLITS > 1)>,                           \
+                gemm_tile_kernel16<BM, BN, WM, WN, true, true, (SPLITS > 1)>,                        \
+                gemm_tile_kernel16<BM, BN, WM, WN, false, false, (SPLITS > 1)>                       \
+        }                                                                                            \
+    }
+
 static const Variant g_variants[] = {
-    {"naive", 0, 0, 256, 0, 0, 1, 0, {nullptr, nullptr, nullptr}},
+    {"naive", 0, 0, 256, 0, 0, 1, 1, 0, {nullptr, nullptr, nullptr}},
     AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2, 1, 1),
     AXONN_TILE_VARIANT("mfma_256x128", 256, 128, 2, 2, 1, 2),
     AXONN_TILE_VARIANT("mfma_128x256", 128, 256, 2, 2, 1, 3),
@@ -120,6 +133,13 @@ static const Variant g_variants[] = {
     // ... or per 128x128 tile (small shard shapes)
     AXONN_TILE_VARIANT("mfma_128x128_sk2", 128, 128, 2, 2, 2, 4),
     AXONN_TILE_VARIANT("mfma_128x128_sk4", 128, 128, 2, 2, 4, 4),
+    // 16x16x32 MFMAs
+    AXONN_TILE_VARIANT16("mfma16_256x256", 256, 256, 2, 2, 1, 8),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8", 256, 256, 2, 4, 1, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_sk2", 256, 256, 2, 2, 2, 8),
+    AXONN_TILE_VARIANT16("mfma16_256x256_sk4", 256, 256, 2, 2, 4, 8),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk2", 256, 256, 2, 4, 2, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk4", 256, 256, 2, 4, 4, 9),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -187,7 +207,7 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
-    if (M % var.bm != 0 || N % var.bn != 0 || K % (KB * var.splits) != 0 || K / var.splits < var.min_k) return false;
+    if (M % var.bm != 0 || N % var.bn != 0 || K % (var.kstep * var.splits) != 0 || K / var.splits < var.min_k) return false;
     if (var.splits == 1) return true;
     // scratch: one flag and one fp32 tile per (tile, extra K range)
     const int64_t slots = (M / var.bm) * (N / var.bn) * (var.splits - 1);
@@ -205,18 +225,19 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
-    static const double eff[3][8] = {
-        /* variant:   naive 256x256 256x128 128x256 128x128, then the 8-wave 256x256 256x128 128x256 */
-        /* NN */ {0.0, 1.00, 0.83, 0.86, 0.77, 1.06, 0.82, 0.86},
-        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95},
+    static const double eff[3][10] = {
+        /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
+         *            16x16x32 256x256 with 4 and 8 waves */
+        /* NN */ {0.0, 1.00, 0.83, 0.86, 0.77, 1.06, 0.82, 0.86, 1.00, 1.12},
+        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 0.96, 1.13},
     };
     constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0, kFixedKSplitSmall = 384.0;
     int best = 0;
     double best_t = 0;
     for (int v = 1; v < kNumVariants; ++v) {
         const Variant& var = g_variants[v];
-        if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split)) continue;
+        if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) continue;
         const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
         // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
         // side by side at half speed each, which comes to the same).  A last round that fills only

@@ -90,6 +90,9 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // the M0-write -> LDS-DMA hazard.  Completion is tracked by vmcnt.  (No immediate offset is used:
 // the hardware would add it to the LDS address as well.)
 __device__ __forceinline__ void direct_load16(uint32_t lds_dst, const uint8_t* base, uint32_t voff) {
+    // wave-uniform by construction; saying so costs nothing where the compiler knows it already and
+    // keeps the operand in an SGPR where its analysis gives up
+    lds_dst = __builtin_amdgcn_readfirstlane(lds_dst);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(base), "s"(lds_dst) : "memory", "m0");
 }
@@ -190,6 +193,7 @@ struct OperandKContig {   // global P[row * ld + k]
     uint32_t lds_par;                          // uniform, PAIR: 1024 when the odd groups are served
     uint32_t step_add;                         // uniform, PAIR: what advance() adds to voff
     uint32_t raddr[2];                         // [substep]: read address of block 0 in stage 0
+    uint32_t raddr16;                          // the same for 16-row blocks read 32 k at a time
 
     // first_step_odd: the first (virtual) K-step of the load schedule serves the odd row groups
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
@@ -218,6 +222,9 @@ struct OperandKContig {   // global P[row * ld + k]
         const uint32_t a0 = lds0 + REGION + row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
         raddr[0] = a0;
         raddr[1] = a0 ^ 32;
+        // 16x16x32 reader: row = wave_row_base + 16*I + lane%16 ((row>>2)&3 = (lane>>2)&3 for every I),
+        // chunk = lane/16
+        raddr16 = lds0 + REGION + (wave_row_base + (lane & 15)) * 64 + ((((lane >> 4) & 3) ^ ((lane >> 2) & 3)) << 4);
     }
     // Load number C of the current K-step (PAIR: for pair C of the row groups now served), for the
     // K-step AHEAD past the window, into the stage at stage_off.
@@ -225,7 +232,7 @@ struct OperandKContig {   // global P[row * ld + k]
     __device__ __forceinline__ void issue(uint32_t stage_off) const {
         static_assert(C < NBASE && (AHEAD == 0 || PAIR), "no such load");
         if constexpr (PAIR)
-            direct_load16(__builtin_amdgcn_readfirstlane(lds_dst[C] + stage_off + lds_par), base[C], voff[AHEAD]);
+            direct_load16(lds_dst[C] + stage_off + lds_par, base[C], voff[AHEAD]);
         else
             direct_load16(lds_dst[C] + stage_off, base[C], voff[0]);
     }
@@ -256,6 +263,16 @@ struct OperandKContig {   // global P[row * ld + k]
     __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
         lds_read128<I * 2048>(f.v, c.a[S]);
     }
+    // fragments of v_mfma_f32_16x16x32_bf16: 16-row block I, all 32 k of the stage (lane l: row l%16,
+    // k = 8*(l/16)..+7)
+    struct Cursor16 {
+        uint32_t a;
+    };
+    __device__ __forceinline__ Cursor16 cursor16(uint32_t stage_off) const { return Cursor16{raddr16 + stage_off}; }
+    template <int I>
+    __device__ __forceinline__ void read16(Frag& f, const Cursor16& c) const {
+        lds_read128<I * 1024>(f.v, c.a);
+    }
 };
 
 template <int ROWS, int REGION, int NW, int NB_>
@@ -275,6 +292,7 @@ struct OperandMNContig {   // global P[k * ld + row]
     uint32_t kstep_bytes;
     uint32_t lds_dst[QL];
     uint32_t raddr[NB];        // [block]: read address in stage 0 for substep 0, first four k
+    uint32_t raddr16[NB];      // [pair of 16-row blocks]: the same for the 16x16x32 fragments
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base, bool /*first_step_odd*/) {
@@ -301,6 +319,14 @@ struct OperandMNContig {   // global P[k * ld + row]
             const uint32_t m = wave_row_base + i * 32 + 16 * (g & 1) + 4 * (sl & 3);
             raddr[i] = lds0 + REGION + (kq + 8 * (g >> 1)) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
         }
+        // 16x16x32 reader: group g covers k = 8g..8g+7 (two reads of four k-rows) for the 16 rows of a
+        // block; lane s of a group addresses k-row (s>>2) and 4 consecutive m at 4*(s&3).  Blocks 2p
+        // and 2p+1 differ by 32 bytes (chunk bit 1, which neither the swizzle nor a carry touches).
+#pragma unroll
+        for (int p = 0; p < NB; ++p) {
+            const uint32_t m = wave_row_base + p * 32 + 4 * (sl & 3);
+            raddr16[p] = lds0 + REGION + (kq + 8 * g) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
+        }
     }
     static constexpr bool PAIR = false;   // a load already covers whole cache lines
     static constexpr int NBASE = QL;
@@ -325,6 +351,20 @@ struct OperandMNContig {   // global P[k * ld + row]
         // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
         lds_read64_tr<(16 * S) * ROWB>(f.lo, c.a[I]);
         lds_read64_tr<(16 * S + 4) * ROWB>(f.hi, c.a[I]);
+    }
+    struct Cursor16 {
+        uint32_t a[NB];
+    };
+    __device__ __forceinline__ Cursor16 cursor16(uint32_t stage_off) const {
+        Cursor16 c;
+#pragma unroll
+        for (int p = 0; p < NB; ++p) c.a[p] = raddr16[p] + stage_off;
+        return c;
+    }
+    template <int I>
+    __device__ __forceinline__ void read16(Frag& f, const Cursor16& c) const {
+        lds_read64_tr<(I & 1) * 32>(f.lo, c.a[I / 2]);
+        lds_read64_tr<(I & 1) * 32 + 4 * ROWB>(f.hi, c.a[I / 2]);
     }
 };
 
@@ -473,15 +513,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     // Nothing may be scheduled across this point (keeps the hand-made instruction order).
 #define AXONN_FENCE() __builtin_amdgcn_sched_barrier(0)
     // MFMA number IDX (i-major) of a half K-step, on fragment buffer BUF.
-    auto mfma = [&](auto buf_c, auto idx_c) {
+    auto mfma = [&](auto buf_c, auto idx_c) __attribute__((always_inline)) {
         constexpr int BUF = decltype(buf_c)::value, I = decltype(idx_c)::value / NI, J = decltype(idx_c)::value % NI;
         acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[BUF][J].get(), fa[BUF][I].get(), acc[I][J], 0, 0, 0);
     };
-    auto mfma_range = [&](auto buf_c, auto lo_c, auto hi_c) {
+    auto mfma_range = [&](auto buf_c, auto lo_c, auto hi_c) __attribute__((always_inline)) {
         constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
-        static_for<HI - LO>([&](auto d) { mfma(buf_c, Int<LO + decltype(d)::value>{}); });
+        static_for<HI - LO>([&](auto d) __attribute__((always_inline)) { mfma(buf_c, Int<LO + decltype(d)::value>{}); });
     };
-    auto wait_fragments = [&](auto buf_c) {
+    auto wait_fragments = [&](auto buf_c) __attribute__((always_inline)) {
         constexpr int BUF = decltype(buf_c)::value;
         tie_to_lds_wait<MI>(fa[BUF]);
         tie_to_lds_wait<NI>(fb[BUF]);
@@ -490,10 +530,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     // the MI + NI blocks (A first) are split evenly over the two clusters.  The buffer being filled
     // was last read by MFMAs of the previous half K-step, all issued before this half began.
     auto read_cluster = [&](auto half_c, auto s_c, auto buf_c, const typename OpA::Cursor& ca,
-                            const typename OpB::Cursor& cb) {
+                            const typename OpB::Cursor& cb) __attribute__((always_inline)) {
         constexpr int H = decltype(half_c)::value, S = decltype(s_c)::value, BUF = decltype(buf_c)::value;
         constexpr int NBLK = MI + NI, FIRST = H == 0 ? 0 : NBLK / 2, LAST = H == 0 ? NBLK / 2 : NBLK;
-        static_for<LAST - FIRST>([&](auto d) {
+        static_for<LAST - FIRST>([&](auto d) __attribute__((always_inline)) {
             constexpr int Q = FIRST + decltype(d)::value;
             if constexpr (Q < MI)
                 opa.template read<Q, S>(fa[BUF][Q], ca);
@@ -512,13 +552,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     // u-NS+2 (any operand paired) are.  KIND: 2 = all of the above, 1 = K-step t+NS-1 no longer
     // exists (a paired operand still fetches its half of t+NS-2), 0 = nothing.
     constexpr bool ANY_PAIR = OpA::PAIR || OpB::PAIR;
-    auto issue_loads = [&](auto op_c, auto kind_c, auto half_c, uint32_t st_near, uint32_t st_far) {
+    auto issue_loads = [&](auto op_c, auto kind_c, auto half_c, uint32_t st_near, uint32_t st_far) __attribute__((always_inline)) {
         constexpr bool IS_A = decltype(op_c)::value == 0;
         constexpr int KIND = decltype(kind_c)::value, H = decltype(half_c)::value;
         using Op = typename std::conditional<IS_A, OpA, OpB>::type;
-        auto& op = [&]() -> auto& { if constexpr (IS_A) return opa; else return opb; }();
+        auto& op = [&]() __attribute__((always_inline)) -> auto& { if constexpr (IS_A) return opa; else return opb; }();
         constexpr int NB = Op::NBASE, FIRST = H == 0 ? 0 : (NB + 1) / 2, LAST = H == 0 ? (NB + 1) / 2 : NB;
-        static_for<LAST - FIRST>([&](auto d) {
+        static_for<LAST - FIRST>([&](auto d) __attribute__((always_inline)) {
             constexpr int C = FIRST + decltype(d)::value;
             if constexpr (Op::PAIR) {
                 if constexpr (KIND >= 1) op.template issue<C, 0>(st_near);
@@ -530,19 +570,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     };
     using Plan = LoadPlan<QA, QB, OpA::PAIR, OpB::PAIR, NS>;
     constexpr int LAG = Plan::LAG;
-    auto next_stage = [&](uint32_t off) -> uint32_t { return off + SB == RING ? 0u : off + SB; };
+    auto next_stage = [&](uint32_t off) __attribute__((always_inline)) -> uint32_t { return off + SB == RING ? 0u : off + SB; };
 
     // ---- prologue: the loads "steps -(NS-1) .. -1" would have issued; K-step 0 visible ----------
-    static_for<NS - 1>([&](auto v) {
+    static_for<NS - 1>([&](auto v) __attribute__((always_inline)) {
         constexpr int T = decltype(v)::value - (NS - 1);          // virtual step
         constexpr uint32_t FAR = (T + NS - 1) * SB;               // stage of K-step T+NS-1
-        static_for<2>([&](auto op_c) {
+        static_for<2>([&](auto op_c) __attribute__((always_inline)) {
             constexpr bool IS_A = decltype(op_c)::value == 0;
             using Op = typename std::conditional<IS_A, OpA, OpB>::type;
-            auto& op = [&]() -> auto& { if constexpr (IS_A) return opa; else return opb; }();
+            auto& op = [&]() __attribute__((always_inline)) -> auto& { if constexpr (IS_A) return opa; else return opb; }();
             if constexpr (Op::PAIR && T == -(NS - 1)) {
                 // K-step -1 does not exist: only the K-step 0 half of the pair, window stays
-                static_for<Op::NBASE>([&](auto d) { op.template issue<decltype(d)::value, 0>(FAR); });
+                static_for<Op::NBASE>([&](auto d) __attribute__((always_inline)) { op.template issue<decltype(d)::value, 0>(FAR); });
                 op.flip();
             } else {
                 constexpr uint32_t NEAR = Op::PAIR ? FAR - SB : 0u;
@@ -570,7 +610,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     //   PHASE: where the two clusters of a half sit among its NM MFMAs.  With two waves per SIMD the
     //         second wave of each SIMD (waves 4..7) uses phase 1, so that one wave's clusters fall
     //         into the other's runs of MFMAs and the matrix pipe always has work queued.
-    auto step = [&](auto phase_c, auto kind_c, auto next_c, auto vm_c) {
+    auto step = [&](auto phase_c, auto kind_c, auto next_c, auto vm_c) __attribute__((always_inline)) {
         constexpr bool NEXT = decltype(next_c)::value;
         constexpr int VM = decltype(vm_c)::value, KIND = decltype(kind_c)::value;
         constexpr int P0 = decltype(phase_c)::value == 0 ? 1 : NM / 4 + 1;        // MFMAs before cluster 0
@@ -630,7 +670,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     // paired (K-step KT-1 still lacks that operand's other half), then kind 0 to the end.
     constexpr int NTAIL = NS - 1;
     const int KT = ktotal / KB;   // at least NS - 1
-    auto main_loop = [&](auto phase_c) {
+    auto main_loop = [&](auto phase_c) __attribute__((always_inline)) {
         // The first fragments are fetched here, inside the phase's own code path: an LDS read is
         // asynchronous and the compiler does not know it, so between a read and the wait that
         // covers it there must be no point (such as a branch join) where it could copy the
@@ -639,7 +679,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         read_cluster(Int<1>{}, Int<0>{}, Int<0>{}, ca, cb);
         constexpr int VM_FULL = Plan::tail_vm(-1);
         for (int kt = KT - NTAIL; kt > 0; --kt) step(phase_c, Int<2>{}, Yes{}, Int<VM_FULL>{});
-        static_for<NTAIL>([&](auto j_c) {
+        static_for<NTAIL>([&](auto j_c) __attribute__((always_inline)) {
             constexpr int J = decltype(j_c)::value;
             step(phase_c, Int<Plan::tail_kind(J)>{}, std::integral_constant<bool, (J + 1 < NTAIL)>{},
                  Int<Plan::tail_vm(J)>{});

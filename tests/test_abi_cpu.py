@@ -84,7 +84,10 @@ def test_variant_table_and_selection():
             assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 32
             assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
             splits = {"sk2": 2, "sk4": 4}.get(names[v].rsplit("_", 1)[-1], 1)
-            assert B.variant_supports(v, 256, 256, 160 * splits, lay)   # per K range
+            assert B.variant_supports(v, 256, 256, 256 * splits, lay)   # per K range
+            kstep = 64 if names[v].startswith("mfma16") else 32         # the 16x16x32 kernels take K-steps in pairs
+            assert B.variant_supports(v, 256, 256, 256 * splits + kstep * splits, lay)
+            assert not B.variant_supports(v, 256, 256, 256 * splits + 32, lay) or (kstep == 32 and splits == 1)
             # split-K keeps (splits - 1) fp32 partial tiles per output tile in a 64 MiB scratch area
             # with 1023 flags
             bm, bn = (int(x) for x in names[v].split("_")[1].split("x"))

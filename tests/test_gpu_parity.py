@@ -51,6 +51,11 @@ def splits_of(v):
     return {"sk2": 2, "sk4": 4}.get(B.variant_name(v).rsplit("_", 1)[-1], 1)
 
 
+def kstep_of(v):
+    """K granularity of a variant: the 16x16x32 kernels consume K-steps of 32 in pairs."""
+    return 64 if B.variant_name(v).startswith("mfma16") else 32
+
+
 def usable(v, M, N, K, layout):
     """Every plain tile variant must take the test shape; a split-K one may decline it."""
     ok = B.variant_supports(v, M, N, K, layout)
@@ -97,22 +102,23 @@ def test_every_tile_variant_against_oracle(oracle_mod, layout):
     # multiple of 8: the plain workgroup -> tile mapping)
     M, N = 768, 768
     for splits in (1, 2, 4):
-        K = 416 * splits
-        a = synth.normal_bf16(31 + splits, (M, K))
-        b = synth.normal_bf16(32 + splits, (K, N), 0.02)
-        A, Bm = store(a, b, layout)
-        ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
-        ran = 0
-        for v in tile_variants():
-            if splits_of(v) != splits:
-                continue
-            assert B.variant_supports(v, M, N, K, layout)
-            got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
-            nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
-            # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
-            assert nw < 4e-3, (B.variant_name(v), nw)
-            ran += 1
-        assert ran >= 2
+        for kstep in (32, 64):   # 13 steps of 32, or 14 for the kernels that take them in pairs
+            K = (416 if kstep == 32 else 448) * splits
+            a = synth.normal_bf16(31 + splits + kstep, (M, K))
+            b = synth.normal_bf16(32 + splits + kstep, (K, N), 0.02)
+            A, Bm = store(a, b, layout)
+            ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+            ran = 0
+            for v in tile_variants():
+                if splits_of(v) != splits or kstep_of(v) != kstep:
+                    continue
+                assert B.variant_supports(v, M, N, K, layout)
+                got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+                nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+                # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
+                assert nw < 4e-3, (B.variant_name(v), nw)
+                ran += 1
+            assert ran >= 2
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
@@ -147,7 +153,7 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
     for v in tile_variants():
         kmin = next(k for k in range(32, 1024, 32) if B.variant_supports(v, M, N, k, layout))
         assert not B.variant_supports(v, M, N, kmin - 32, layout)
-        for K in (kmin, kmin + 32 * splits_of(v)):
+        for K in (kmin, kmin + kstep_of(v) * splits_of(v)):
             a = synth.normal_bf16(41 + K, (M, K))
             b = synth.normal_bf16(42 + K, (K, N))
             A, Bm = store(a, b, layout)
@@ -198,7 +204,7 @@ def test_caller_owned_workspace(oracle_mod):
 # ------------------------------------------------------------------ exact integers: bit for bit
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_integer_inputs_are_bit_exact(oracle_mod, layout):
-    M, N, K = 512, 768, 640   # rectangular, 2 x 3 tiles of 256, 20 K-steps (5 per range when split in 4)
+    M, N, K = 512, 768, 1536   # rectangular, 2 x 3 tiles of 256, 48 K-steps (12 per range when split in 4)
     a = synth.integer_bf16(51, (M, K), -4, 4)
     b = synth.integer_bf16(52, (K, N), -4, 4)
     A, Bm = store(a, b, layout)
