@@ -243,8 +243,8 @@ int axonn_linear_copy_probe(const void *src, void *dst, size_t bytes, void *stre
 /* Measurement aid: the matrix-pipe ceiling for a given operand distribution.  Launches
  * `workgroups` workgroups of 4 waves; every wave reads 32 operand fragments once from `data`
  * (DEVICE pointer, 16-byte aligned, at least 128 KiB of bf16 values, the same for all workgroups)
- * and then issues iters * 64 bf16 MFMAs (32x32x16) on registers only: iters * 64 * 32768 flops per
- * wave, no memory traffic.  `sink` is a DEVICE pointer to one float (never written in practice).
+ * and then issues iters * 128 bf16 MFMAs (16x16x32, the instruction of the default tile kernels) on
+ * registers only: iters * 64 * 32768 flops per wave, no memory traffic.  `sink` is a DEVICE pointer to one float (never written in practice).
  * Time it with events; with one workgroup per compute unit this is what the kernels above could
  * reach if operands were free.  Returns AXONN_OK, AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
 int axonn_linear_mfma_probe(const void *data, size_t data_bytes, int iters, int workgroups,

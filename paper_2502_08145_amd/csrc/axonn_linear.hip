@@ -46,38 +46,43 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
-// Nothing but MFMAs: every wave keeps 16 + 16 operand fragments (read once from `data`) and 16
-// accumulator blocks in registers and issues `iters` x 64 v_mfma_f32_32x32x16_bf16, in the same
-// operand pattern as the 256x256 tile kernel (4 A x 4 B fragments per k16 substep).  It measures the
+// Nothing but MFMAs: every wave keeps 16 + 16 operand fragments (read once from `data`) and 64
+// accumulator blocks in registers and issues `iters` x 128 v_mfma_f32_16x16x32_bf16, in the same
+// operand pattern as the 256x256 tile kernel on 16x16x32 MFMAs (8 A x 8 B fragments per K-step).  It measures the
 // matrix-pipe ceiling for a given operand distribution: on MI355X the sustained clock, and with it
 // this ceiling, depends on how much the operand bits toggle.
 __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict__ data, float* __restrict__ sink,
                                                          int iters) {
-    bf16x8 a[16], b[16];
+    typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+    bf16x8 a[16], b[16];   // two K-steps' worth of 8 + 8 fragments of 16 rows x 32 k
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         a[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * i]);
         b[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * (16 + i)]);
     }
-    f32x16 acc[16];
+    probe_f32x4 acc[64];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int i = 0; i < 64; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < iters; ++it) {
+        // eight MFMAs per asm statement (one A fragment against the eight B fragments of its K-step):
+        // a clean issue stream, accumulators pinned in AGPRs
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[s * 4 + j], a[s * 4 + i], acc[i * 4 + j], 0, 0, 0);
+            for (int i = 0; i < 8; ++i)
+                asm volatile(
+                    "v_mfma_f32_16x16x32_bf16 %0, %8, %16, %0\n\tv_mfma_f32_16x16x32_bf16 %1, %9, %16, %1\n\t"
+                    "v_mfma_f32_16x16x32_bf16 %2, %10, %16, %2\n\tv_mfma_f32_16x16x32_bf16 %3, %11, %16, %3\n\t"
+                    "v_mfma_f32_16x16x32_bf16 %4, %12, %16, %4\n\tv_mfma_f32_16x16x32_bf16 %5, %13, %16, %5\n\t"
+                    "v_mfma_f32_16x16x32_bf16 %6, %14, %16, %6\n\tv_mfma_f32_16x16x32_bf16 %7, %15, %16, %7"
+                    : "+a"(acc[i * 8 + 0]), "+a"(acc[i * 8 + 1]), "+a"(acc[i * 8 + 2]), "+a"(acc[i * 8 + 3]),
+                      "+a"(acc[i * 8 + 4]), "+a"(acc[i * 8 + 5]), "+a"(acc[i * 8 + 6]), "+a"(acc[i * 8 + 7])
+                    : "v"(b[s * 8 + 0]), "v"(b[s * 8 + 1]), "v"(b[s * 8 + 2]), "v"(b[s * 8 + 3]), "v"(b[s * 8 + 4]),
+                      "v"(b[s * 8 + 5]), "v"(b[s * 8 + 6]), "v"(b[s * 8 + 7]), "v"(a[s * 8 + i]));
     }
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    for (int i = 0; i < 64; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
     if (t == 12345.678f) sink[0] = t;   // keeps the accumulators live; practically never taken
 }
 
@@ -140,6 +145,12 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT16("mfma16_256x256_sk4", 256, 256, 2, 2, 4, 8),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk2", 256, 256, 2, 4, 2, 9),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk4", 256, 256, 2, 4, 4, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x128", 256, 128, 2, 2, 1, 10),
+    AXONN_TILE_VARIANT16("mfma16_128x256", 128, 256, 2, 2, 1, 11),
+    AXONN_TILE_VARIANT16("mfma16_128x256_w8", 128, 256, 2, 4, 1, 12),
+    AXONN_TILE_VARIANT16("mfma16_128x128", 128, 128, 2, 2, 1, 13),
+    AXONN_TILE_VARIANT16("mfma16_128x128_sk2", 128, 128, 2, 2, 2, 13),
+    AXONN_TILE_VARIANT16("mfma16_128x128_sk4", 128, 128, 2, 2, 4, 13),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -225,12 +236,12 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
-    static const double eff[3][10] = {
+    static const double eff[3][14] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
-         *            16x16x32 256x256 with 4 and 8 waves */
-        /* NN */ {0.0, 1.00, 0.83, 0.86, 0.77, 1.06, 0.82, 0.86, 1.00, 1.12},
-        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 0.96, 1.13},
+         *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128 */
+        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85},
+        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90},
     };
     constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0, kFixedKSplitSmall = 384.0;
     int best = 0;

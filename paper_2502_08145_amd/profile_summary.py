@@ -20,12 +20,12 @@ import sys
 
 
 def short(name: str) -> str:
-    m = re.search(r"gemm_tile_kernel<(\d+), (\d+), (\d+), (\d+), (true|false), (true|false), (true|false)>", name)
+    m = re.search(r"gemm_tile_kernel(16)?<(\d+), (\d+), (\d+), (\d+), (true|false), (true|false), (true|false)>", name)
     if m:
-        bm, bn, wm, wn, akc, bkc, split = m.groups()
+        k16, bm, bn, wm, wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
         waves = "_w8" if int(wm) * int(wn) == 8 else ""
-        return f"mfma_{bm}x{bn}{waves}{'_sk' if split == 'true' else ''}/{lay}"
+        return f"mfma{k16 or ''}_{bm}x{bn}{waves}{'_sk' if split == 'true' else ''}/{lay}"
     if "copy_probe_kernel" in name:
         return "copy_probe"
     if "gemm_naive_kernel" in name:
@@ -45,7 +45,7 @@ def summarize(d: str, out=sys.stdout):
         for r in csv.DictReader(open(f)):
             ctr[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
     print(f"== {d}", file=out)
-    keys = [k for k in dur if k.startswith(("mfma_", "copy_probe", "naive"))]
+    keys = [k for k in dur if k.startswith(("mfma", "copy_probe", "naive"))]
     for k in sorted(keys, key=lambda k: -sum(dur[k])):
         v = dur[k]
         print(f"{k:<22s} calls {len(v):5d}  mean {sum(v) / len(v) / 1e3:9.2f} us  min {min(v) / 1e3:9.2f}  "
@@ -71,7 +71,7 @@ def traffic(workload: str, copy_mib: float, fetch_dir: str, write_dir: str) -> d
     w_scale = kib / mean(write["copy_probe"]["WRITE_SIZE"])
     out = {}
     for k in fetch:
-        if k.startswith("mfma_") and k in write:
+        if k.startswith("mfma") and k in write:
             out[k] = int(round(1024.0 * (mean(fetch[k]["FETCH_SIZE"]) * f_scale + mean(write[k]["WRITE_SIZE"]) * w_scale)))
     return {workload: out, "_scale": {"FETCH_SIZE": round(f_scale, 4), "WRITE_SIZE": round(w_scale, 4)},
             "_note": "bytes per launch = FETCH_SIZE x scale + WRITE_SIZE x scale (KiB -> bytes), scales from the copy probe"}
