@@ -227,9 +227,22 @@ int axonn_linear_num_variants(void);
 const char *axonn_linear_variant_name(int variant);
 /* 1 if `variant` can run (M,N,K,layout), else 0. */
 int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout);
-/* The variant the library would pick for this problem (pure host logic, ignores any override);
- * negative error code on bad arguments. */
+/* The variant the library would pick for ONE launch over the whole output (pure host logic,
+ * ignores any override); negative error code on bad arguments. */
 int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout);
+/* The launches the library makes for this problem when no variant is forced.  An output whose
+ * tiles fill the 256 compute units a whole number of times and then only part of them is cut
+ * into two blocks (the second holds the last rows or the last columns), each with the variant
+ * that suits it, e.g. the large tile for the first and split-K for the second.  Block i covers
+ * rows row0 .. row0+m-1 and columns col0 .. col0+n-1 of the M x N output; the blocks are
+ * disjoint and cover it.  Writes parts[0 .. return value - 1] (HOST memory, caller-owned, room
+ * for 2) and returns the number of launches, 1 or 2; negative error code on bad arguments.
+ * Pure host logic. */
+typedef struct {
+    int variant;
+    int64_t m, n, row0, col0;
+} axonn_plan_part_t;
+int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[2]);
 /* Override the choice for all later calls in this process; -1 restores automatic selection.
  * Returns AXONN_OK or AXONN_ERR_INVALID_ARG.  For tests, tuning and the benchmark. */
 int axonn_linear_force_variant(int variant);

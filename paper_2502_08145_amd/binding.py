@@ -23,6 +23,7 @@ EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
+    "axonn_linear_plan",
     "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
     "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
@@ -31,6 +32,12 @@ EXPORTS = (
 )
 
 _lib = None
+
+
+class PlanPart(ctypes.Structure):
+    """axonn_plan_part_t"""
+    _fields_ = [("variant", ctypes.c_int), ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+                ("row0", ctypes.c_int64), ("col0", ctypes.c_int64)]
 
 
 class TuneResult(ctypes.Structure):
@@ -91,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_variant_supports.restype = ci
         L.axonn_linear_select_variant.argtypes = [i64, i64, i64, ci]
         L.axonn_linear_select_variant.restype = ci
+        L.axonn_linear_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(PlanPart)]
+        L.axonn_linear_plan.restype = ci
         L.axonn_linear_force_variant.argtypes = [ci]
         L.axonn_linear_force_variant.restype = ci
         L.axonn_linear_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
@@ -151,6 +160,20 @@ def variant_supports(v: int, M: int, N: int, K: int, layout) -> bool:
 
 def select_variant(M: int, N: int, K: int, layout) -> int:
     return lib().axonn_linear_select_variant(M, N, K, _layout(layout))
+
+
+def plan(M: int, N: int, K: int, layout) -> list:
+    """The launches behind one product: a list of dicts(variant, m, n, row0, col0), one or two."""
+    parts = (PlanPart * 2)()
+    n = lib().axonn_linear_plan(M, N, K, _layout(layout), parts)
+    if n < 0:
+        raise AxonnError(n, "axonn_linear_plan")
+    return [dict(variant=p.variant, m=p.m, n=p.n, row0=p.row0, col0=p.col0) for p in parts[:n]]
+
+
+def plan_name(M: int, N: int, K: int, layout) -> str:
+    """Variant names of the launches of plan(), joined by '+'."""
+    return "+".join(variant_name(p["variant"]) for p in plan(M, N, K, layout))
 
 
 def force_variant(v: int) -> None:

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <map>
 #include <mutex>
@@ -89,7 +90,9 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict
 // ------------------------------------------------------------------------------------------
 // Variant table
 // ------------------------------------------------------------------------------------------
-typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int, SplitK);
+// (A, B, C, K, lda, ldb, ldc, tiles_m, tiles_n, group_m, split-K state): leading dimensions in elements of
+// the operands as stored, so that a launch can cover a block of rows or columns of a larger product
+typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int, int, SplitK);
 
 struct Variant {
     const char* name;
@@ -235,7 +238,7 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // K-contiguous operands are the dearer ones to stage (64-byte row segments per load), which is
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
-static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
+static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
     static const double eff[3][14] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
          *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128 */
@@ -244,30 +247,97 @@ static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allo
         /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90},
     };
     constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0, kFixedKSplitSmall = 384.0;
+    const Variant& var = g_variants[v];
+    if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) return -1.0;
+    const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
+    // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
+    // side by side at half speed each, which comes to the same).  A last round that fills only
+    // a fraction f of the CUs runs faster than a full one (the busy CUs get the idle ones'
+    // power and bandwidth): measured about 0.5 + 0.5 f of a full round.
+    const int64_t full = wgs / 256, rest = wgs % 256;
+    // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
+    if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) return -1.0;
+    const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
+    const double k_cost = (double)(K / var.splits) +
+                          (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedKSplitSmall
+                           : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
+    return rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
+}
+
+// The variant with the smallest modelled time for one launch over the whole output (0, the naive
+// kernel, if no tile shape divides it); *t_out receives that time.
+static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split, double* t_out = nullptr) {
     int best = 0;
     double best_t = 0;
     for (int v = 1; v < kNumVariants; ++v) {
-        const Variant& var = g_variants[v];
-        if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) continue;
-        const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
-        // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
-        // side by side at half speed each, which comes to the same).  A last round that fills only
-        // a fraction f of the CUs runs faster than a full one (the busy CUs get the idle ones'
-        // power and bandwidth): measured about 0.5 + 0.5 f of a full round.
-        const int64_t full = wgs / 256, rest = wgs % 256;
-        // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
-        if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) continue;
-        const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
-        const double k_cost = (double)(K / var.splits) +
-                              (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedKSplitSmall
-                               : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
-        const double t = rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
-        if (best == 0 || t < best_t) {
+        const double t = model_time(v, M, N, K, layout, allow_split);
+        if (t >= 0.0 && (best == 0 || t < best_t)) {
             best = v;
             best_t = t;
         }
     }
+    if (t_out) *t_out = best_t;
     return best;
+}
+
+// A product as one launch, or as two launches over disjoint blocks of the output.  An output of,
+// say, 384 large tiles keeps the 256 CUs busy for one round and half of them for a second; cut
+// into a block of 256 tiles and a block of 128, the second block can run as split-K (or on a
+// smaller tile) and fill the chip again.  The cut runs along N (the second block holds the last
+// columns) or along M (the last rows); operand and output blocks are addressed through the leading
+// dimensions of the whole matrices.
+struct Part {
+    int variant;
+    int64_t m, n, row0, col0;
+};
+struct Plan {
+    int parts;
+    Part part[2];
+};
+
+static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
+    double t_one = 0;
+    Plan plan{1, {{select_variant(M, N, K, layout, allow_split, &t_one), M, N, 0, 0}, {0, 0, 0, 0, 0}}};
+    // nothing to gain within one round of large tiles: split-K and the smaller tiles cover that
+    if (plan.part[0].variant == 0 || M % 128 != 0 || N % 128 != 0 || (M / 128) * (N / 128) <= 4 * 256) return plan;
+    // what a second launch costs beyond its own fill and drain (the first one's tail is not
+    // overlapped), in the model's units: about 3 us
+    constexpr double kSecondLaunch = 8.0e6;
+    // a two-launch plan must be clearly better: the model is good to a few per cent
+    double best_t = t_one * 0.97;
+    auto consider = [&](bool along_n, int64_t rest) {
+        const int64_t m1 = along_n ? M : M - rest, n1 = along_n ? N - rest : N;
+        const int64_t m2 = along_n ? M : rest, n2 = along_n ? rest : N;
+        double t1 = 0, t2 = 0;
+        const int v1 = select_variant(m1, n1, K, layout, allow_split, &t1);
+        const int v2 = select_variant(m2, n2, K, layout, allow_split, &t2);
+        if (v1 == 0 || v2 == 0 || t1 + t2 + kSecondLaunch >= best_t) return;
+        best_t = t1 + t2 + kSecondLaunch;
+        plan = Plan{2, {{v1, m1, n1, 0, 0}, {v2, m2, n2, along_n ? 0 : m1, along_n ? n1 : 0}}};
+    };
+    // second blocks of up to half a round of large tiles, in steps of one tile column / row
+    const int64_t step_n = N % 256 == 0 ? 256 : 128, step_m = M % 256 == 0 ? 256 : 128;
+    for (int64_t rest = step_n; rest < N && M * rest <= (int64_t)128 * 256 * 256; rest += step_n) consider(true, rest);
+    for (int64_t rest = step_m; rest < M && rest * N <= (int64_t)128 * 256 * 256; rest += step_m) consider(false, rest);
+    return plan;
+}
+
+// Plans are remembered per shape: the search above costs a few hundred model evaluations.
+static std::map<std::tuple<int64_t, int64_t, int64_t, int, bool>, Plan> g_plans;
+static std::mutex g_plans_mutex;
+
+static Plan cached_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
+    const auto key = std::make_tuple(M, N, K, layout, allow_split);
+    {
+        std::lock_guard<std::mutex> lock(g_plans_mutex);
+        const auto it = g_plans.find(key);
+        if (it != g_plans.end()) return it->second;
+    }
+    const Plan plan = make_plan(M, N, K, layout, allow_split);
+    std::lock_guard<std::mutex> lock(g_plans_mutex);
+    if (g_plans.size() >= 4096) g_plans.clear();
+    g_plans[key] = plan;
+    return plan;
 }
 
 static int check_args(int64_t M, int64_t N, int64_t K, int layout, const void* a, const void* b,
@@ -295,34 +365,63 @@ static void raise_lds_limits() {
     (void)hipGetLastError();
 }
 
+static size_t split_bytes(const Part& p) {
+    const Variant& x = g_variants[p.variant];
+    return x.bm == 0 ? 0 : (size_t)((p.m / x.bm) * (p.n / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
+}
+
+static size_t split_bytes(const Plan& plan) {
+    size_t bytes = 0;
+    for (int i = 0; i < plan.parts; ++i) bytes = std::max(bytes, split_bytes(plan.part[i]));
+    return bytes;   // the launches of a plan run one after the other and share the area
+}
+
+// One tile-kernel launch over the block `p` of the M x N output.
+static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layout, const uint16_t* A, const uint16_t* B,
+                        uint16_t* C, const Scratch& scratch, hipStream_t s) {
+    const Variant& var = g_variants[p.variant];
+    const int64_t lda = layout == AXONN_TN ? M : K, ldb = layout == AXONN_NT ? K : N, ldc = N;
+    A += layout == AXONN_TN ? p.row0 : p.row0 * K;
+    B += layout == AXONN_NT ? p.col0 * K : p.col0;
+    C += p.row0 * N + p.col0;
+    const int tiles_m = (int)(p.m / var.bm), tiles_n = (int)(p.n / var.bn);
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int group_m = tiles_m < 8 ? tiles_m : 8;
+    SplitK sk{nullptr, nullptr, nullptr, 0u, 1};
+    if (var.splits > 1) {
+        uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
+        if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;   // flags start at 0
+        sk = SplitK{scratch.partials, scratch.flags, scratch.timeouts(), epoch, var.splits};
+    }
+    hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)(tiles * var.splits)), dim3(var.threads), var.lds_bytes, s,
+                       A, B, C, (int)K, (int)lda, (int)ldb, (int)ldc, tiles_m, tiles_n, group_m, sk);
+}
+
 static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, const void* b, void* c,
                   int fp32_accumulate, void* stream) {
     const int rc = check_args(M, N, K, layout, a, b, c, fp32_accumulate);
     if (rc != AXONN_OK) return rc;
     if (M == 0 || N == 0) return AXONN_OK;
 
-    int v = g_forced.load(std::memory_order_relaxed);
+    const int forced = g_forced.load(std::memory_order_relaxed);
+    Plan plan;
     Scratch scratch;
-    auto bytes_needed = [&](int variant) {
-        const Variant& x = g_variants[variant];
-        return (size_t)((M / x.bm) * (N / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
-    };
-    if (v >= 0) {
-        if (!variant_supports(v, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch(bytes_needed(v))).partials) return AXONN_ERR_WORKSPACE;
+    if (forced >= 0) {
+        if (!variant_supports(forced, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
+        plan = Plan{1, {{forced, M, N, 0, 0}, {0, 0, 0, 0, 0}}};
+        if (split_bytes(plan) && !(scratch = get_scratch(split_bytes(plan))).partials) return AXONN_ERR_WORKSPACE;
     } else {
-        v = select_variant(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
-        if (g_variants[v].splits > 1 && !(scratch = get_scratch(bytes_needed(v))).partials)
-            v = select_variant(M, N, K, layout, false);
+        plan = cached_plan(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
+        if (split_bytes(plan) && !(scratch = get_scratch(split_bytes(plan))).partials)
+            plan = cached_plan(M, N, K, layout, false);
     }
-    const Variant& var = g_variants[v];
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t* A = static_cast<const uint16_t*>(a);
     const uint16_t* B = static_cast<const uint16_t*>(b);
     uint16_t* C = static_cast<uint16_t*>(c);
 
     (void)hipGetLastError();
-    if (var.bm == 0) {
+    if (g_variants[plan.part[0].variant].bm == 0) {
         const dim3 grid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16));
         if (grid.y > 65535u * 16u) return AXONN_ERR_UNSUPPORTED;
         switch (layout) {
@@ -332,18 +431,11 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
         }
     } else {
         std::call_once(g_attr_once, raise_lds_limits);
-        const int tiles_m = (int)(M / var.bm), tiles_n = (int)(N / var.bn);
-        const int64_t tiles = (int64_t)tiles_m * tiles_n;
-        if (tiles >= ((int64_t)1 << 31)) return AXONN_ERR_UNSUPPORTED;
-        const int group_m = tiles_m < 8 ? tiles_m : 8;
-        SplitK sk{nullptr, nullptr, nullptr, 0u, 1};
-        if (var.splits > 1) {
-            uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
-            if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;   // flags start at 0
-            sk = SplitK{scratch.partials, scratch.flags, scratch.timeouts(), epoch, var.splits};
+        for (int i = 0; i < plan.parts; ++i) {
+            const Variant& var = g_variants[plan.part[i].variant];
+            if ((plan.part[i].m / var.bm) * (plan.part[i].n / var.bn) >= ((int64_t)1 << 31) / var.splits) return AXONN_ERR_UNSUPPORTED;
         }
-        hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)(tiles * var.splits)), dim3(var.threads), var.lds_bytes, s,
-                           A, B, C, (int)M, (int)N, (int)K, tiles_m, tiles_n, group_m, sk);
+        for (int i = 0; i < plan.parts; ++i) launch_part(plan.part[i], M, N, K, layout, A, B, C, scratch, s);
     }
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
@@ -498,6 +590,14 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
     return axonn::select_variant(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
 }
 
+int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[2]) {
+    if (M <= 0 || N <= 0 || K < 0 || layout < 0 || layout > 2 || !parts) return AXONN_ERR_INVALID_ARG;
+    const axonn::Plan plan = axonn::cached_plan(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
+    for (int i = 0; i < plan.parts; ++i)
+        parts[i] = axonn_plan_part_t{plan.part[i].variant, plan.part[i].m, plan.part[i].n, plan.part[i].row0, plan.part[i].col0};
+    return plan.parts;
+}
+
 int axonn_linear_init(void) {
     std::call_once(axonn::g_attr_once, axonn::raise_lds_limits);
     return axonn::get_scratch(axonn::kSlotBytes).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
@@ -505,10 +605,8 @@ int axonn_linear_init(void) {
 
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout) {
     if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return 0;
-    const int v = axonn::select_variant(M, N, K, layout, true);
-    const axonn::Variant& var = axonn::g_variants[v];
-    if (var.splits == 1) return 0;
-    return axonn::kFlagBytes + (size_t)((M / var.bm) * (N / var.bn) * (var.splits - 1)) * var.bm * var.bn * sizeof(float);
+    const size_t bytes = axonn::split_bytes(axonn::cached_plan(M, N, K, layout, true));
+    return bytes ? axonn::kFlagBytes + bytes : 0;
 }
 
 int axonn_linear_set_workspace(void* dev_ptr, size_t bytes) {

@@ -71,7 +71,7 @@ struct LoadPlan16 {
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
-    int M, int N, int K, int tiles_m, int tiles_n, int group_m, SplitK sk) {
+    int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n, int group_m, SplitK sk) {
     using Cfg = TileCfg16<BM, BN, WM, WN>;
     constexpr int NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS, NTAIL = Cfg::NTAIL;
@@ -123,8 +123,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     const int64_t k0 = (int64_t)krange * ktotal;
     // the load schedule starts NS K-steps before K-step 0
     constexpr bool FIRST_ODD = NS % 2 == 1;
-    opa.init(A + (A_KC ? k0 : k0 * M), m0, 2u * (uint32_t)(A_KC ? K : M), lane, wave, lds0, wm * TM, FIRST_ODD);
-    opb.init(B + (B_KC ? k0 : k0 * N), n0, 2u * (uint32_t)(B_KC ? K : N), lane, wave, lds0, wn * TN, FIRST_ODD);
+    opa.init(A + (A_KC ? k0 : k0 * lda), m0, 2u * (uint32_t)lda, lane, wave, lds0, wm * TM, FIRST_ODD);
+    opb.init(B + (B_KC ? k0 : k0 * ldb), n0, 2u * (uint32_t)ldb, lane, wave, lds0, wn * TN, FIRST_ODD);
 
     f32x4 acc[MI][NI];
 #pragma unroll
@@ -370,13 +370,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
         AXONN_FENCE();   // convert block row by block row: keeps register pressure low
     }
     __syncthreads();
-    uint16_t* pc = C + (m0 + wm * TM) * (int64_t)N + n0 + wn * TN;
+    uint16_t* pc = C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN;
 #pragma unroll
     for (int it = 0; it < (TM * CPR) / 64; ++it) {
         const uint32_t idx = it * 64 + lane;
         const uint32_t row = idx / CPR, ch = idx % CPR;
         const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
-        *reinterpret_cast<u32x4*>(pc + (int64_t)row * N + ch * 8) = v;
+        *reinterpret_cast<u32x4*>(pc + (int64_t)row * ldc + ch * 8) = v;
     }
 #undef AXONN_FENCE
 }

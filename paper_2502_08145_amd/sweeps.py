@@ -59,7 +59,7 @@ def peak_curve(args):
             reps = int(max(4, min(100, 2000.0 / max(est, 1e-3))))
             ms = time_gemm("fwd", n, n, n, layout, a, b, c, reps)
             tf = 2.0 * n ** 3 / ms / 1e9
-            v = B.variant_name(B.select_variant(n, n, n, layout))
+            v = B.plan_name(n, n, n, layout)
             print(f"{n:6d} {layout:>4s} {v:<22s} {reps:4d} {ms:10.4f} {tf:9.1f} {tf / PEAK * 100:6.1f}%", flush=True)
         del a, b, c
         n *= 2

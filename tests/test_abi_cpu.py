@@ -154,3 +154,55 @@ def test_tuner_host_side():
     assert L.axonn_linear_tune(0, 256, 256, 256, 0, ALIGNED, ALIGNED, None, 0, None, ctypes.byref(res)) == bad
     assert L.axonn_linear_tune(0, 256, 256, 256, ALIGNED, ALIGNED, ALIGNED, ALIGNED + 16, 1 << 20, None, ctypes.byref(res)) == bad
     assert L.axonn_linear_tune(0, 256, 256, 256, ALIGNED, ALIGNED, ALIGNED, None, 0, None, None) == bad
+
+
+# ------------------------------------------------------------------ launch plans (host logic)
+@pytest.mark.parametrize("shape", [(2048, 12288, 4096), (12288, 2048, 4096), (4096, 5120, 4096), (6144, 6144, 6144),
+                                   (2048, 16384, 4096), (2048, 4096, 4096), (256, 256, 256), (100, 100, 64),
+                                   (2560, 8192, 1024), (2048, 10240, 1024), (128, 65536, 512)])
+@pytest.mark.parametrize("layout", ["NN", "NT", "TN"])
+def test_plan_blocks_tile_the_output_and_their_variants_fit(shape, layout):
+    M, N, K = shape
+    parts = B.plan(M, N, K, layout)
+    assert 1 <= len(parts) <= 2
+    first = parts[0]
+    assert (first["row0"], first["col0"]) == (0, 0)
+    if len(parts) == 1:
+        assert (first["m"], first["n"]) == (M, N)
+        assert first["variant"] == B.select_variant(M, N, K, layout)
+    else:
+        second = parts[1]
+        if second["col0"]:      # cut along N
+            assert first["m"] == second["m"] == M and second["row0"] == 0
+            assert second["col0"] == first["n"] and first["n"] + second["n"] == N
+        else:                   # cut along M
+            assert first["n"] == second["n"] == N and second["col0"] == 0
+            assert second["row0"] == first["m"] and first["m"] + second["m"] == M
+        # operand and output blocks start on 16-byte boundaries in every layout
+        assert second["row0"] % 8 == 0 and second["col0"] % 8 == 0
+    for p in parts:
+        assert p["variant"] > 0 or len(parts) == 1
+        assert B.variant_supports(p["variant"], p["m"], p["n"], K, layout)
+
+
+def test_plan_cuts_one_and_a_half_rounds_and_leaves_whole_rounds_alone():
+    # 384 tiles of 256x256 on 256 compute units: a block of 256 tiles, then the other 128
+    parts = B.plan(2048, 12288, 4096, "NN")
+    assert [(p["m"], p["n"]) for p in parts] == [(2048, 8192), (2048, 4096)]
+    assert B.variant_name(parts[0]["variant"]).endswith("256x256_w8")
+    # 512 tiles: two whole rounds, one launch; 128 tiles: one launch (split-K or a smaller tile)
+    assert len(B.plan(2048, 16384, 4096, "NN")) == 1
+    assert len(B.plan(2048, 4096, 4096, "NN")) == 1
+    # the workspace a caller must bring covers the split-K block of a plan
+    parts = B.plan(2048, 12288, 4096, "NT")
+    assert B.variant_name(parts[1]["variant"]).endswith("sk2")
+    assert B.axonn_linear_workspace_bytes(2048, 12288, 4096, "NT") == 4096 + 128 * 256 * 256 * 4
+
+
+def test_plan_rejects_bad_arguments():
+    import ctypes
+    L = B.lib()
+    parts = (B.PlanPart * 2)()
+    assert L.axonn_linear_plan(0, 128, 128, 0, parts) == B.AXONN_ERR_INVALID_ARG
+    assert L.axonn_linear_plan(128, 128, 128, 3, parts) == B.AXONN_ERR_INVALID_ARG
+    assert L.axonn_linear_plan(128, 128, 128, 0, ctypes.cast(None, ctypes.POINTER(B.PlanPart))) == B.AXONN_ERR_INVALID_ARG

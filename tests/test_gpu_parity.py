@@ -335,6 +335,48 @@ def test_square_layout_sweep_sampled(oracle_mod, n):
         U.assert_close(got[ii, jj], ref, f"square {n} {layout}")
 
 
+# ------------------------------------------------------------------ products cut into two launches
+@pytest.mark.parametrize("shape", [(2048, 10240, 1024), (2560, 8192, 1024)])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_two_launch_plans_every_element(oracle_mod, layout, shape):
+    """Outputs of one and a quarter rounds of large tiles: the library cuts off the last columns
+    (first shape) or the last rows (second shape) into a launch of their own; every element checked."""
+    M, N, K = shape
+    parts = B.plan(M, N, K, layout)
+    assert len(parts) == 2, parts
+    assert (parts[1]["col0"] > 0) == (shape[1] == 10240) and (parts[1]["row0"] > 0) == (shape[0] == 2560)
+    a = synth.normal_bf16(synth.BASE_SEED + 700, (M, K))
+    b = synth.normal_bf16(synth.BASE_SEED + 701, (K, N))
+    A, Bm = store(a, b, layout)
+    ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+    got = run_gpu("fwd", M, N, K, layout, A, Bm)
+    U.assert_close(got, ref, f"two launches {shape} {layout}")
+    # integer-valued operands: bit for bit, whichever launch wrote the element
+    ai = synth.integer_bf16(synth.BASE_SEED + 702, (M, K), -4, 4)
+    bi = synth.integer_bf16(synth.BASE_SEED + 703, (K, N), -4, 4)
+    A, Bm = store(ai, bi, layout)
+    got = run_gpu("fwd", M, N, K, layout, A, Bm)
+    assert np.array_equal(got, U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm)))
+
+
+@pytest.mark.parametrize("shape", [(2048, 12288, 4096), (12288, 2048, 4096)])
+def test_two_launch_plan_with_split_k_block_sampled(oracle_mod, shape):
+    """One round and a half of large tiles at a long K: the second block runs as split-K (NT),
+    reading its operands and writing its output through the whole matrices' leading dimensions."""
+    M, N, K = shape
+    parts = B.plan(M, N, K, "NT")
+    assert len(parts) == 2 and B.variant_name(parts[1]["variant"]).rsplit("_", 1)[-1] in ("sk2", "sk4"), parts
+    a = synth.normal_bf16(synth.BASE_SEED + 710, (M, K))
+    b = synth.normal_bf16(synth.BASE_SEED + 711, (K, N))
+    ii, jj = _sample_positions(M, N, seed=M + 7)
+    ref = oracle_mod.gemm_at(M, N, K, "NN", a, b, ii, jj)
+    for layout in LAYOUTS:
+        A, Bm = store(a, b, layout)
+        got = run_gpu("fwd", M, N, K, layout, A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all(), f"{shape} {layout}: unwritten or non-finite output"
+        U.assert_close(got[ii, jj], ref, f"two launches, split-K block {shape} {layout}")
+
+
 # ------------------------------------------------------------------ operand re-storage (transpose)
 @pytest.mark.parametrize("shape", [(64, 64), (128, 192), (4096, 1024), (2048, 12288), (1, 7), (65, 130),
                                    (257, 31), (64, 72), (1000, 8)])
