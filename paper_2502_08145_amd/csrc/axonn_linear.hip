@@ -246,7 +246,7 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
         /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72},
         /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90},
     };
-    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0, kFixedKSplitSmall = 384.0;
+    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0;
     const Variant& var = g_variants[v];
     if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) return -1.0;
     const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
@@ -258,8 +258,13 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
     if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) return -1.0;
     const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
+    // the exchange of a small tile is latency: the reader takes the partial tiles one after the
+    // other once the writers are done, and it grows with the number of tiles in flight
+    // (measured: 4 us + 0.055 us per tile for two K ranges, 7 us + 0.17 us per tile for four)
+    const double tiles = (double)((M / var.bm) * (N / var.bn));
+    const double fixed_small = var.splits == 2 ? 700.0 + 8.0 * tiles : 1300.0 + 25.0 * tiles;
     const double k_cost = (double)(K / var.splits) +
-                          (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedKSplitSmall
+                          (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedK + fixed_small
                            : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
     return rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
 }

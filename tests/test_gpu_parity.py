@@ -322,7 +322,7 @@ def test_full_size_layers_sampled(oracle_mod, name, tokens, d_in, d_out):
             U.assert_close(got[ii, jj], ref, f"{g['name']} {layout}")
 
 
-@pytest.mark.parametrize("n", [4096, 8192])
+@pytest.mark.parametrize("n", [4096, 8192, 16384])
 def test_square_layout_sweep_sampled(oracle_mod, n):
     a = synth.normal_bf16(synth.BASE_SEED + 500, (n, n))
     b = synth.normal_bf16(synth.BASE_SEED + 501, (n, n))
