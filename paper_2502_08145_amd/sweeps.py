@@ -93,9 +93,9 @@ def model_zoo(args):
                         flops_sum += fl
                         ms_sum += ms
                         if worst is None or tf < worst[0]:
-                            worst = (tf, f"{name}.{op} {lay} M={M} N={N} K={K} {B.variant_name(v)}")
+                            worst = (tf, f"{name}.{op} {lay} M={M} N={N} K={K} {B.plan_name(M, N, K, lay)}")
                         if args.verbose:
-                            print(f"   {h} {name}.{op} {lay} M={M} N={N} K={K} {B.variant_name(v)} {ms * 1e3:.1f} us {tf:.0f}", flush=True)
+                            print(f"   {h} {name}.{op} {lay} M={M} N={N} K={K} {B.plan_name(M, N, K, lay)} {ms * 1e3:.1f} us {tf:.0f}", flush=True)
                     del X, W, dY
         rates.sort()
         print(f"{h:6d} {len(rates):5d} {guarded:7d} {rates[0]:8.1f} {rates[len(rates) // 2]:8.1f} {rates[-1]:8.1f} "
