@@ -253,11 +253,12 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
     // side by side at half speed each, which comes to the same).  A last round that fills only
     // a fraction f of the CUs runs faster than a full one (the busy CUs get the idle ones'
-    // power and bandwidth): measured about 0.5 + 0.5 f of a full round.
+    // power and bandwidth): measured about 0.6 + 0.4 f of a full round (0.61 at 4 workgroups,
+    // 0.78 at 128, 0.87 at 144).
     const int64_t full = wgs / 256, rest = wgs % 256;
     // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
     if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) return -1.0;
-    const double rounds = (double)full + (rest ? 0.5 + 0.5 * (double)rest / 256.0 : 0.0);
+    const double rounds = (double)full + (rest ? 0.6 + 0.4 * (double)rest / 256.0 : 0.0);
     // the exchange of a small tile is latency: the reader takes the partial tiles one after the
     // other once the writers are done, and it grows with the number of tiles in flight
     // (measured: 4 us + 0.055 us per tile for two K ranges, 7 us + 0.17 us per tile for four)
@@ -303,8 +304,8 @@ struct Plan {
 static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
     double t_one = 0;
     Plan plan{1, {{select_variant(M, N, K, layout, allow_split, &t_one), M, N, 0, 0}, {0, 0, 0, 0, 0}}};
-    // nothing to gain within one round of large tiles: split-K and the smaller tiles cover that
-    if (plan.part[0].variant == 0 || M % 128 != 0 || N % 128 != 0 || (M / 128) * (N / 128) <= 4 * 256) return plan;
+    // nothing to gain within half a round of large tiles: split-K and the smaller tiles cover that
+    if (plan.part[0].variant == 0 || M % 128 != 0 || N % 128 != 0 || (M / 128) * (N / 128) <= 4 * 128) return plan;
     // what a second launch costs beyond its own fill and drain (the first one's tail is not
     // overlapped), in the model's units: about 3 us
     constexpr double kSecondLaunch = 8.0e6;

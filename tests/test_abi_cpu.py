@@ -159,7 +159,8 @@ def test_tuner_host_side():
 # ------------------------------------------------------------------ launch plans (host logic)
 @pytest.mark.parametrize("shape", [(2048, 12288, 4096), (12288, 2048, 4096), (4096, 5120, 4096), (6144, 6144, 6144),
                                    (2048, 16384, 4096), (2048, 4096, 4096), (256, 256, 256), (100, 100, 64),
-                                   (2560, 8192, 1024), (2048, 10240, 1024), (128, 65536, 512)])
+                                   (2560, 8192, 1024), (2048, 10240, 1024), (128, 65536, 512), (2048, 4608, 18432),
+                                   (2048, 6144, 49152)])
 @pytest.mark.parametrize("layout", ["NN", "NT", "TN"])
 def test_plan_blocks_tile_the_output_and_their_variants_fit(shape, layout):
     M, N, K = shape

@@ -359,10 +359,12 @@ def test_two_launch_plans_every_element(oracle_mod, layout, shape):
     assert np.array_equal(got, U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm)))
 
 
-@pytest.mark.parametrize("shape", [(2048, 12288, 4096), (12288, 2048, 4096)])
+@pytest.mark.parametrize("shape", [(2048, 12288, 4096), (12288, 2048, 4096), (2048, 4608, 18432)])
 def test_two_launch_plan_with_split_k_block_sampled(oracle_mod, shape):
     """One round and a half of large tiles at a long K: the second block runs as split-K (NT),
-    reading its operands and writing its output through the whole matrices' leading dimensions."""
+    reading its operands and writing its output through the whole matrices' leading dimensions.
+    Third shape: 144 large tiles, less than a round; both blocks run as split-K, one after the
+    other through the same scratch area."""
     M, N, K = shape
     parts = B.plan(M, N, K, "NT")
     assert len(parts) == 2 and B.variant_name(parts[1]["variant"]).rsplit("_", 1)[-1] in ("sk2", "sk4"), parts
