@@ -95,6 +95,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     int krange = 0, ktotal = K;
     if constexpr (SPLITK) {
         const int splits = sk.splits, tiles = tiles_m * tiles_n;
+        if (BM * BN == 256 * 256 && splits == 4 && (nwg & 7) == 0 && K >= kSplitRangePerXcdK) {
+            // Long K: XCDs 0-1 take the last K range, ..., XCDs 6-7 range 0, each a contiguous chunk
+            // of the tiles, so the 32 workgroups that share an L2 read the same K slices (with
+            // all four ranges of a tile on one XCD they would share a quarter as much; measured
+            // 17-20 % faster at K = 65536 for NN and NT).  The readers then sit on two XCDs only,
+            // which makes the exchange slower by some 10 us: not for short K.  Writers keep the
+            // lower workgroup ids (same pid >> 3, lower XCD).
+            const int x = pid & 7, q = pid >> 3, tp = tiles >> 1;
+            krange = 3 - (x >> 1);
+            pid = (x & 1) * tp + q;
+        } else
         if (nwg % (8 * splits) == 0) {
             const int tp = (nwg >> 3) / splits, li = pid >> 3;
             krange = splits - 1 - li / tp;

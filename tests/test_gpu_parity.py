@@ -145,6 +145,30 @@ def test_split_k_xcd_mapping_and_repeated_launches(oracle_mod, layout):
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
+@pytest.mark.parametrize("shape", [(512, 512, 32768), (256, 512, 32768), (768, 256, 32768)])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_split_k_long_k_one_range_per_xcd_pair(oracle_mod, layout, shape):
+    # From K = 32768 on, the 256x256 kernels with four K ranges give each pair of XCDs one range
+    # (workgroup count a multiple of 8: 4 and 2 tiles; 3 tiles fall back to the plain order).
+    # Integer data: exact under any order of the partial sums (|sum| <= 16 K < 2^24).
+    M, N, K = shape
+    a = synth.integer_bf16(95, (M, K), -4, 4)
+    b = synth.integer_bf16(96, (K, N), -4, 4)
+    A, Bm = store(a, b, layout)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
+    ran = 0
+    for v in tile_variants():
+        if splits_of(v) != 4 or "256x256" not in B.variant_name(v):
+            continue
+        assert B.variant_supports(v, M, N, K, layout)
+        for rep in range(2):
+            got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+            assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
+        ran += 1
+    assert ran == 4
+    assert B.axonn_linear_split_k_timeouts() == 0
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_shortest_k_and_single_tile(oracle_mod, layout):
     # the shortest K each tile kernel takes (its prologue fills the whole LDS ring, the main loop
@@ -377,6 +401,23 @@ def test_two_launch_plan_with_split_k_block_sampled(oracle_mod, shape):
         got = run_gpu("fwd", M, N, K, layout, A, Bm)
         assert np.isfinite(U.bits_to_f64(got)).all(), f"{shape} {layout}: unwritten or non-finite output"
         U.assert_close(got[ii, jj], ref, f"two launches, split-K block {shape} {layout}")
+
+
+def test_long_k_four_ranges_full_chip_sampled(oracle_mod):
+    """64 large tiles at K = 32768: four K ranges per tile on all 256 compute units, one range per
+    pair of XCDs (the configuration the shard shapes of the widest models run in)."""
+    M, N, K = 2048, 2048, 32768
+    assert all(B.plan_name(M, N, K, lay).endswith("256x256_w8_sk4") for lay in LAYOUTS)
+    a = synth.normal_bf16(synth.BASE_SEED + 720, (M, K))
+    b = synth.normal_bf16(synth.BASE_SEED + 721, (K, N))
+    ii, jj = _sample_positions(M, N, seed=K)
+    ref = oracle_mod.gemm_at(M, N, K, "NN", a, b, ii, jj)
+    for layout in LAYOUTS:
+        A, Bm = store(a, b, layout)
+        got = run_gpu("bwd_data", M, N, K, layout, A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all()
+        U.assert_close(got[ii, jj], ref, f"long K, four ranges {layout}")
+    assert B.axonn_linear_split_k_timeouts() == 0
 
 
 # ------------------------------------------------------------------ operand re-storage (transpose)
