@@ -154,6 +154,10 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT16("mfma16_128x128", 128, 128, 2, 2, 1, 13),
     AXONN_TILE_VARIANT16("mfma16_128x128_sk2", 128, 128, 2, 2, 2, 13),
     AXONN_TILE_VARIANT16("mfma16_128x128_sk4", 128, 128, 2, 2, 4, 13),
+    // other numbers of K ranges (the kernels take the count at run time): 3 for outputs of 65-85 large
+    // tiles, 8 for at most 32
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk3", 256, 256, 2, 4, 3, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk8", 256, 256, 2, 4, 8, 9),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -246,7 +250,7 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
         /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72},
         /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90},
     };
-    constexpr double kFixedK = 128.0, kFixedKSplit4 = 1024.0, kFixedKSplit8 = 512.0;
+    constexpr double kFixedK = 128.0;
     const Variant& var = g_variants[v];
     if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) return -1.0;
     const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
@@ -264,9 +268,12 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // (measured: 4 us + 0.055 us per tile for two K ranges, 7 us + 0.17 us per tile for four)
     const double tiles = (double)((M / var.bm) * (N / var.bn));
     const double fixed_small = var.splits == 2 ? 700.0 + 8.0 * tiles : 1300.0 + 25.0 * tiles;
-    const double k_cost = (double)(K / var.splits) +
-                          (var.splits == 1 ? kFixedK : var.bm * var.bn <= 128 * 128 ? kFixedK + fixed_small
-                           : var.threads == 256 ? kFixedKSplit4 : kFixedKSplit8);
+    // large tiles: the partial tiles travel through HBM, (splits - 1) x 256 KB per tile written and
+    // read back at 4-5 TB/s: 0.115 us, or 4.6 units of k, per slot (the 4-wave kernels exchange
+    // more slowly)
+    const double fixed_large = (var.threads == 256 ? 640.0 : 128.0) + 4.6 * tiles * (var.splits - 1);
+    const double k_cost = (double)(K / var.splits) + kFixedK +
+                          (var.splits == 1 ? 0.0 : var.bm * var.bn <= 128 * 128 ? fixed_small : fixed_large);
     return rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
 }
 

@@ -79,11 +79,12 @@ def test_variant_table_and_selection():
         assert B.variant_supports(0, 3, 5, 7, lay)
         for v in range(1, n):
             assert not B.variant_supports(v, 100, 200, 300, lay)
-            assert B.variant_supports(v, 1024, 1024, 1024, lay)
+            assert B.variant_supports(v, 1024, 1024, 1536, lay)
             assert not B.variant_supports(v, 1024, 1024, 1000, lay)
             assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 32
             assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
-            splits = {"sk2": 2, "sk4": 4}.get(names[v].rsplit("_", 1)[-1], 1)
+            tail = names[v].rsplit("_", 1)[-1]
+            splits = int(tail[2:]) if tail.startswith("sk") else 1
             assert B.variant_supports(v, 256, 256, 256 * splits, lay)   # per K range
             kstep = 64 if names[v].startswith("mfma16") else 32         # the 16x16x32 kernels take K-steps in pairs
             assert B.variant_supports(v, 256, 256, 256 * splits + kstep * splits, lay)
@@ -115,7 +116,7 @@ def test_variant_table_and_selection():
 def test_workspace_queries_are_host_only():
     # split-K problems need 4 KiB of flags plus one fp32 tile per (tile, extra K range)
     assert B.axonn_linear_workspace_bytes(2048, 4096, 16384, "NT") == 4096 + 128 * 256 * 256 * 4
-    assert B.axonn_linear_workspace_bytes(2048, 2048, 8192, "NN") == 4096 + 64 * 3 * 256 * 256 * 4
+    assert B.axonn_linear_workspace_bytes(2048, 2048, 32768, "NN") == 4096 + 64 * 3 * 256 * 256 * 4
     assert B.axonn_linear_workspace_bytes(8192, 8192, 8192, "TN") == 0
     assert B.axonn_linear_workspace_bytes(100, 200, 300, "NN") == 0
     assert B.axonn_linear_workspace_bytes(0, 8, 8, "NN") == 0
@@ -195,9 +196,9 @@ def test_plan_cuts_one_and_a_half_rounds_and_leaves_whole_rounds_alone():
     assert len(B.plan(2048, 16384, 4096, "NN")) == 1
     assert len(B.plan(2048, 4096, 4096, "NN")) == 1
     # the workspace a caller must bring covers the split-K block of a plan
-    parts = B.plan(2048, 12288, 4096, "NT")
+    parts = B.plan(2048, 12288, 8192, "NT")
     assert B.variant_name(parts[1]["variant"]).endswith("sk2")
-    assert B.axonn_linear_workspace_bytes(2048, 12288, 4096, "NT") == 4096 + 128 * 256 * 256 * 4
+    assert B.axonn_linear_workspace_bytes(2048, 12288, 8192, "NT") == 4096 + 128 * 256 * 256 * 4
 
 
 def test_plan_rejects_bad_arguments():
