@@ -155,8 +155,11 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT16("mfma16_128x128_sk2", 128, 128, 2, 2, 2, 13),
     AXONN_TILE_VARIANT16("mfma16_128x128_sk4", 128, 128, 2, 2, 4, 13),
     // other numbers of K ranges (the kernels take the count at run time): 3 for outputs of 65-85 large
-    // tiles, 8 for at most 32
+    // tiles, ..., 8 for at most 32
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk3", 256, 256, 2, 4, 3, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk5", 256, 256, 2, 4, 5, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk6", 256, 256, 2, 4, 6, 9),
+    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk7", 256, 256, 2, 4, 7, 9),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk8", 256, 256, 2, 4, 8, 9),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
@@ -269,9 +272,10 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     const double tiles = (double)((M / var.bm) * (N / var.bn));
     const double fixed_small = var.splits == 2 ? 700.0 + 8.0 * tiles : 1300.0 + 25.0 * tiles;
     // large tiles: the partial tiles travel through HBM, (splits - 1) x 256 KB per tile written and
-    // read back at 4-5 TB/s: 0.115 us, or 4.6 units of k, per slot (the 4-wave kernels exchange
-    // more slowly)
-    const double fixed_large = (var.threads == 256 ? 640.0 : 128.0) + 4.6 * tiles * (var.splits - 1);
+    // read back at 4-5 TB/s (0.1 us, or 4 units of k, per slot), and the reader of a tile takes its
+    // slots one after the other at one CU's rate (2.5 us, 100 units, per slot); the 4-wave
+    // kernels exchange more slowly
+    const double fixed_large = (var.threads == 256 ? 512.0 : 0.0) + 4.0 * tiles * (var.splits - 1) + 100.0 * (var.splits - 1);
     const double k_cost = (double)(K / var.splits) + kFixedK +
                           (var.splits == 1 ? 0.0 : var.bm * var.bn <= 128 * 128 ? fixed_small : fixed_large);
     return rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
