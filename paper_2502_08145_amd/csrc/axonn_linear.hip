@@ -13,6 +13,7 @@
 
 #include "gemm_mfma.hpp"
 #include "gemm_mfma16.hpp"
+#include "gemm_mfma16_k64.hpp"
 #include "comm_model.hpp"
 #include "transpose.hpp"
 
@@ -124,6 +125,14 @@ struct Variant {
         }                                                                                            \
     }
 
+// the NT-only kernel with 64-k LDS stages (4 waves)
+#define AXONN_TILE_VARIANT_K64(NAME, SPLITS, BASE)                                                   \
+    {                                                                                                \
+        NAME, 256, 256, TileCfgK64::NT, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, SPLITS, BASE, { \
+            nullptr, gemm_tile_kernel_k64<(SPLITS > 1)>, nullptr                                     \
+        }                                                                                            \
+    }
+
 static const Variant g_variants[] = {
     {"naive", 0, 0, 256, 0, 0, 1, 1, 0, {nullptr, nullptr, nullptr}},
     AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2, 1, 1),
@@ -161,6 +170,12 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk6", 256, 256, 2, 4, 6, 9),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk7", 256, 256, 2, 4, 7, 9),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk8", 256, 256, 2, 4, 8, 9),
+    // NT only: 64-k LDS stages
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256", 1, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk2", 2, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk3", 3, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk4", 4, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk8", 8, 14),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -227,6 +242,7 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     if (v < 0 || v >= kNumVariants || layout < 0 || layout > 2) return false;
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
+    if (!var.fn[layout]) return false;   // a kernel for one layout only
     if (M <= 0 || N <= 0 || K <= 0) return false;
     if (M % var.bm != 0 || N % var.bn != 0 || K % (var.kstep * var.splits) != 0 || K / var.splits < var.min_k) return false;
     if (var.splits == 1) return true;
@@ -246,12 +262,13 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
 static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
-    static const double eff[3][14] = {
+    static const double eff[3][15] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
-         *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128 */
-        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85},
-        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90},
+         *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128,
+         *            the 64-k NT kernel */
+        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85, 0.0},
+        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72, 1.12},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90, 0.0},
     };
     constexpr double kFixedK = 128.0;
     const Variant& var = g_variants[v];
@@ -274,7 +291,7 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // large tiles: the partial tiles travel through HBM, (splits - 1) x 256 KB per tile written and
     // read back at 4-5 TB/s (0.1 us, or 4 units of k, per slot), and the reader of a tile takes its
     // slots one after the other at one CU's rate (2.5 us, 100 units, per slot); the 4-wave
-    // kernels exchange more slowly
+    // kernels exchange more slowly (half as many waves keep stores and loads in flight)
     const double fixed_large = (var.threads == 256 ? 512.0 : 0.0) + 4.0 * tiles * (var.splits - 1) + 100.0 * (var.splits - 1);
     const double k_cost = (double)(K / var.splits) + kFixedK +
                           (var.splits == 1 ? 0.0 : var.bm * var.bn <= 128 * 128 ? fixed_small : fixed_large);
@@ -377,7 +394,8 @@ static int check_args(int64_t M, int64_t N, int64_t K, int layout, const void* a
 static void raise_lds_limits() {
     for (int v = 1; v < kNumVariants; ++v)
         for (int l = 0; l < 3; ++l)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(g_variants[v].fn[l]),
+            if (g_variants[v].fn[l])
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(g_variants[v].fn[l]),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, g_variants[v].lds_bytes);
     (void)hipGetLastError();
 }
