@@ -1,14 +1,15 @@
-// The NT product (both operands K-contiguous in memory: A[m][k], B[n][k]) with LDS stages of 64 k.
+// The tile kernel with LDS stages of 64 k, four waves and one barrier per 64 k.
 //
 // Why a kernel of its own.  In gemm_tile_kernel16 a K-contiguous operand is staged 32 k at a time:
 // a row of a stage is 64 bytes, half a cache line, so every direct load asks the L1 for sixteen
-// half lines, and the 8-wave layout reads every LDS byte three times.  With both operands
-// K-contiguous the panels can instead be staged 64 k at a time:
+// half lines, and the 8-wave layout reads every LDS byte three times.  Here:
 //
-//  * an LDS row is one whole 128-byte line (row r, the eight 16-byte chunks XOR-swizzled by
-//    (r>>1)&7: ds_read_b128 of sixteen consecutive rows then touches every bank once), a direct
-//    load fetches 8 rows x 128 B: eight full-line requests instead of sixteen half-line ones;
-//  * two buffers of (256 + 256) rows x 128 B = 64 KB each; 4 waves (2 x 2), wave tile 128 x 128:
+//  * a K-contiguous panel is staged 64 k at a time: an LDS row is one whole 128-byte line (row r,
+//    the eight 16-byte chunks XOR-swizzled by (r>>1)&7: ds_read_b128 of sixteen consecutive rows
+//    then touches every bank once), a direct load fetches 8 rows x 128 B: eight full-line requests
+//    instead of sixteen half-line ones.  An MN-contiguous panel is two 32-k stages of
+//    OperandMNContig side by side;
+//  * two buffers of (256 + 256) x 64 k = 64 KB each; 4 waves (2 x 2), wave tile 128 x 128:
 //    every LDS byte is read twice, not three times;
 //  * ONE barrier per 64 k.  An iteration is two sub-steps of 32 k (64 MFMAs per wave each).  During
 //    sub-step 0 of iteration i the fragments of its sub-step 1 are read; during sub-step 1, after
@@ -17,8 +18,10 @@
 //    load issued so far must have landed (vmcnt(0)): those of iteration i+1, issued one iteration
 //    earlier, i.e. a lead of almost two sub-steps.
 //
-// Fragments, MFMA order (mfma(Bfrag, Afrag)), accumulator layout, split-K exchange, epilogue and
-// the XCD-aware tile order are those of gemm_tile_kernel16.
+// It pays where both operands are K-contiguous (NT: 5-8 % faster than the 8-wave kernel); for NN it
+// ties and for TN it loses 5 %, so the selection uses it for NT.  Fragments, MFMA order
+// (mfma(Bfrag, Afrag)), accumulator layout, split-K exchange, epilogue and the XCD-aware tile order
+// are those of gemm_tile_kernel16.
 #pragma once
 #include "gemm_mfma16.hpp"
 
@@ -32,8 +35,99 @@ struct TileCfgK64 {
     static constexpr int MIN_K = 2 * KS;                           // the prologue fills both buffers
 };
 
+// Operand policies of the 64-k kernel: a wave issues eight direct loads per operand and iteration.
+//   issue<X>(buf)        load X (0..7) of the iteration at the global window, into the buffer at buf
+//   advance()            window one iteration (64 k) on
+//   cursor(S, buf)       read addresses for sub-step S of that buffer
+//   read<I>(frag, cur)   fragment of 16-row block I
+template <int REGION>
+struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks swizzled by (row>>1)&7
+    using Frag = Frag128;
+    struct Cursor {
+        uint32_t a;
+    };
+    const uint8_t* base[8];   // uniform: row group 8*wave + c (8 rows each), k = 0
+    uint32_t lds_dst;         // uniform: destination of group 8*wave inside buffer 0
+    uint32_t voff[2];         // per lane, [group parity]: row-in-group * ld + fetched chunk * 16 + window
+    uint32_t raddr[2];        // [sub-step]: read address of block 0 in buffer 0
+
+    // Lane l of a load lands at (row l/8, slot l%8) of its group; slot s of row r holds chunk
+    // s ^ ((r>>1)&7), and (r>>1)&7 = 4*(group&1) + l/16.  A reader lane wants, for block I and
+    // sub-step S, row 16*I + l%16 and chunk 4*S + l/16, found in slot (4*S + l/16) ^ ((l%16)>>1);
+    // block I is an immediate offset of I * 2048.
+    __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
+                                         uint32_t lds0, int wave_row_base) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            base[c] = reinterpret_cast<const uint8_t*>(P) + (size_t)(row0 + 8 * (8 * wave + c)) * ld_bytes;
+        lds_dst = lds0 + REGION + (uint32_t)(8 * wave) * 1024u;
+        const uint32_t r16 = lane & 15, quad = lane >> 4;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            voff[p] = (uint32_t)(lane >> 3) * ld_bytes + ((((uint32_t)lane & 7u) ^ (4u * p + quad)) << 4);
+            raddr[p] = lds0 + REGION + (uint32_t)(wave_row_base + r16) * 128u + (((4u * p + quad) ^ (r16 >> 1)) << 4);
+        }
+    }
+    template <int X>
+    __device__ __forceinline__ void issue(uint32_t buf) const {
+        direct_load16(lds_dst + buf + X * 1024u, base[X], voff[X & 1]);
+    }
+    __device__ __forceinline__ void advance() {
+        voff[0] += 128;
+        voff[1] += 128;
+    }
+    template <int S>
+    __device__ __forceinline__ Cursor cursor(uint32_t buf) const {
+        return Cursor{raddr[S] + buf};
+    }
+    template <int I>
+    __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
+        lds_read128<I * 2048>(f.v, c.a);
+    }
+};
+
+template <int REGION>
+struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32-k stages of OperandMNContig
+    using Inner = OperandMNContig<256, REGION, 4, 4>;
+    using Frag = typename Inner::Frag;
+    using Cursor = typename Inner::Cursor16;
+    static constexpr uint32_t HALF = 256 * KB * 2;   // bytes of one 32-k stage
+    static_assert(Inner::QL == 4, "four loads per wave and 32-k stage");
+    Inner in;
+    uint32_t voff_hi[2];      // the window of the second stage
+
+    __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
+                                         uint32_t lds0, int wave_row_base) {
+        in.init(P, row0, ld_bytes, lane, wave, lds0, wave_row_base, false);
+        voff_hi[0] = in.voff[0] + in.kstep_bytes;
+        voff_hi[1] = in.voff[1] + in.kstep_bytes;
+    }
+    template <int X>
+    __device__ __forceinline__ void issue(uint32_t buf) const {
+        constexpr int C = X % 4;
+        if constexpr (X < 4)
+            direct_load16(in.lds_dst[C] + buf, in.base[C], in.voff[C & 1]);
+        else
+            direct_load16(in.lds_dst[C] + buf + HALF, in.base[C], voff_hi[C & 1]);
+    }
+    __device__ __forceinline__ void advance() {
+        in.voff[0] += 2 * in.kstep_bytes;
+        in.voff[1] += 2 * in.kstep_bytes;
+        voff_hi[0] += 2 * in.kstep_bytes;
+        voff_hi[1] += 2 * in.kstep_bytes;
+    }
+    template <int S>
+    __device__ __forceinline__ Cursor cursor(uint32_t buf) const {
+        return in.cursor16(buf + S * HALF);
+    }
+    template <int I>
+    __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
+        in.template read16<I>(f, c);
+    }
+};
+
 // Requires M % 256 == 0, N % 256 == 0, K % 64 == 0, K >= 128 (per K range when split).
-template <bool SPLITK>
+template <bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n, int group_m, SplitK sk) {
@@ -82,58 +176,34 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int64_t k0 = (int64_t)krange * ktotal;
 
-    // ---- direct loads: this wave fetches row groups 8*wave .. 8*wave+7 of either operand ------------
-    // Lane l of a load lands at (row l/8, slot l%8) of its group; slot s of row r holds chunk
-    // s ^ ((r>>1)&7), and (r>>1)&7 = 4*(group&1) + l/16: one per-lane offset for the even groups and
-    // one for the odd ones.
+    // ---- operands ------------------------------------------------------------------------------------
+    using OpA = typename std::conditional<A_KC, OperandK64KContig<0>, OperandK64MNContig<0>>::type;
+    using OpB = typename std::conditional<B_KC, OperandK64KContig<REGION_B>, OperandK64MNContig<REGION_B>>::type;
     const uint32_t lds0 = lds_address(smem);
-    const uint32_t lda_b = 2u * (uint32_t)lda, ldb_b = 2u * (uint32_t)ldb;
-    const uint8_t* base_a[QL];
-    const uint8_t* base_b[QL];
-#pragma unroll
-    for (int c = 0; c < QL; ++c) {
-        base_a[c] = reinterpret_cast<const uint8_t*>(A + k0) + (size_t)(m0 + 8 * (QL * wave + c)) * lda_b;
-        base_b[c] = reinterpret_cast<const uint8_t*>(B + k0) + (size_t)(n0 + 8 * (QL * wave + c)) * ldb_b;
-    }
-    const uint32_t lds_dst_a = lds0 + (uint32_t)(QL * wave) * 1024u, lds_dst_b = lds_dst_a + REGION_B;
-    uint32_t voff_a[2], voff_b[2];   // [group parity]; advance 128 bytes per iteration
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const uint32_t chunk = (uint32_t)(lane & 7) ^ (uint32_t)(4 * p + (lane >> 4));
-        voff_a[p] = (uint32_t)(lane >> 3) * lda_b + (chunk << 4);
-        voff_b[p] = (uint32_t)(lane >> 3) * ldb_b + (chunk << 4);
-    }
-    // load number X of an iteration (0..7: A groups, 8..15: B groups) into the buffer at `buf`
+    OpA opa;
+    OpB opb;
+    opa.init(A + (A_KC ? k0 : k0 * lda), m0, 2u * (uint32_t)lda, lane, wave, lds0, wm * TM);
+    opb.init(B + (B_KC ? k0 : k0 * ldb), n0, 2u * (uint32_t)ldb, lane, wave, lds0, wn * TN);
+    // load number X of an iteration (0..7: A, 8..15: B) into the buffer at `buf`
     auto issue = [&](auto x_c, uint32_t buf) __attribute__((always_inline)) {
-        constexpr int X = decltype(x_c)::value, G = X % QL;
+        constexpr int X = decltype(x_c)::value;
         if constexpr (X < QL)
-            direct_load16(lds_dst_a + buf + G * 1024u, base_a[G], voff_a[G & 1]);
+            opa.template issue<X>(buf);
         else
-            direct_load16(lds_dst_b + buf + G * 1024u, base_b[G], voff_b[G & 1]);
+            opb.template issue<X - QL>(buf);
     };
     auto advance_window = [&]() __attribute__((always_inline)) {
-        voff_a[0] += 2 * Cfg::KS; voff_a[1] += 2 * Cfg::KS;
-        voff_b[0] += 2 * Cfg::KS; voff_b[1] += 2 * Cfg::KS;
+        opa.advance();
+        opb.advance();
     };
-
-    // ---- fragment reads: lane l wants, for 16-row block I and sub-step s, row 16*I + l%16 and chunk
-    // 4*s + l/16; that chunk sits in slot (4*s + l/16) ^ ((l%16)>>1).  Block I is an immediate offset
-    // of I * 2048.
-    const uint32_t r16 = lane & 15, quad = lane >> 4;
-    uint32_t raddr_a[2], raddr_b[2];   // [sub-step]
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const uint32_t slot = ((uint32_t)(4 * s) + quad) ^ (r16 >> 1);
-        raddr_a[s] = lds0 + (uint32_t)(wm * TM + r16) * 128u + (slot << 4);
-        raddr_b[s] = lds0 + REGION_B + (uint32_t)(wn * TN + r16) * 128u + (slot << 4);
-    }
 
     f32x4 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    Frag128 fa[2][MI], fb[2][NI];   // [sub-step][block]; pinned registers (see lds_read128)
+    typename OpA::Frag fa[2][MI];   // [sub-step][block]; pinned registers (see lds_read128)
+    typename OpB::Frag fb[2][NI];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
@@ -169,14 +239,14 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
 #define AXONN_K64_LAST 47
 #endif
     constexpr int NC = AXONN_K64_NC, PER = 16 / NC;
-    auto read_cluster = [&](auto q_c, auto s_c, uint32_t addr_a, uint32_t addr_b) __attribute__((always_inline)) {
+    auto read_cluster = [&](auto q_c, auto s_c, const typename OpA::Cursor& ca, const typename OpB::Cursor& cb) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
         static_for<PER>([&](auto d) __attribute__((always_inline)) {
             constexpr int X = PER * Q + decltype(d)::value;
             if constexpr (X < MI)
-                lds_read128<X * 2048>(fa[S][X].v, addr_a);
+                opa.template read<X>(fa[S][X], ca);
             else
-                lds_read128<(X - MI) * 2048>(fb[S][X - MI].v, addr_b);
+                opb.template read<X - MI>(fb[S][X - MI], cb);
         });
     };
     auto load_cluster = [&](auto q_c, uint32_t buf) __attribute__((always_inline)) {
@@ -208,22 +278,16 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
         AXONN_FENCE();
         mfma_range(s_c, Int<0>{}, Int<PB>{});
         AXONN_FENCE();
-        uint32_t addr_a = 0, addr_b = 0;
-        if constexpr (READ) {
-            if constexpr (S == 1) {
-                wait_vmcnt<0>();                 // the next iteration's panels: every load of this wave ...
-                __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffer is free
-                AXONN_FENCE();
-                addr_a = raddr_a[0] + (cur ^ BUF);
-                addr_b = raddr_b[0] + (cur ^ BUF);
-            } else {
-                addr_a = raddr_a[1] + cur;
-                addr_b = raddr_b[1] + cur;
-            }
+        typename OpA::Cursor ca = opa.template cursor<1 - S>(S == 1 ? cur ^ BUF : cur);
+        typename OpB::Cursor cb = opb.template cursor<1 - S>(S == 1 ? cur ^ BUF : cur);
+        if constexpr (READ && S == 1) {
+            wait_vmcnt<0>();                 // the next iteration's panels: every load of this wave ...
+            __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffer is free
+            AXONN_FENCE();
         }
         static_for<NC>([&](auto q_c) __attribute__((always_inline)) {
             constexpr int Q = decltype(q_c)::value;
-            if constexpr (READ) read_cluster(q_c, Int<1 - S>{}, addr_a, addr_b);
+            if constexpr (READ) read_cluster(q_c, Int<1 - S>{}, ca, cb);
             if constexpr (LOAD) load_cluster(q_c, cur);
             AXONN_FENCE();
             if constexpr (Q < NC - 1)
@@ -239,7 +303,11 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     using No = std::false_type;
 
     // fragments of iteration 0, sub-step 0
-    static_for<NC>([&](auto q_c) __attribute__((always_inline)) { read_cluster(q_c, Int<0>{}, raddr_a[0], raddr_b[0]); });
+    {
+        const typename OpA::Cursor ca = opa.template cursor<0>(0u);
+        const typename OpB::Cursor cb = opb.template cursor<0>(0u);
+        static_for<NC>([&](auto q_c) __attribute__((always_inline)) { read_cluster(q_c, Int<0>{}, ca, cb); });
+    }
     const int KI = ktotal / Cfg::KS;   // at least 2
     for (int it = KI - 2; it > 0; --it) {
         substep(Int<0>{}, Yes{}, No{});
@@ -301,6 +369,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
     // acc[i][j][e] = C[m = i*16 + l%16][n = j*16 + 4*(l/16) + e]
     constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile
+    const uint32_t r16 = lane & 15, quad = lane >> 4;
     constexpr uint32_t CMASK = CPR - 1;
     uint8_t* epi = smem + wave * (TM * TN * 2);
 #pragma unroll

@@ -43,10 +43,8 @@ def run_gpu(op, M, N, K, layout, A_bits, B_bits, variant=-1, stream=None, poison
 
 
 def tile_variants(layout=None):
-    """All MFMA tile variants; with a layout, those that have a kernel for it (the 64-k kernel,
-    mfma16k64_*, exists for NT only)."""
-    return [v for v in range(1, B.num_variants())
-            if layout is None or layout == "NT" or not B.variant_name(v).startswith("mfma16k64")]
+    """All MFMA tile variants (every one has a kernel for every layout)."""
+    return [v for v in range(1, B.num_variants())]
 
 
 def splits_of(v):
@@ -171,7 +169,7 @@ def test_split_k_long_k_one_range_per_xcd_pair(oracle_mod, layout, shape):
             got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
             assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
         ran += 1
-    assert ran == (5 if layout == "NT" else 4)
+    assert ran == 5
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
