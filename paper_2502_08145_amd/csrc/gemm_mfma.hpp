@@ -169,8 +169,14 @@ __device__ __forceinline__ void tie_to_lds_wait(Frag64x2* f) {
 //   read<I, S>(frag, cursor)   fragment of 32-row block I, k16 substep S (0/1)
 // The stage offset is the only run-time part of an LDS address; everything else is an immediate.
 // ------------------------------------------------------------------------------------------------
-template <int ROWS, int REGION, int NW, int NB_>
+// SWZ: the four 16-byte chunks of LDS row r are XOR-swizzled by (r >> SWZ) & 3.  ds_read_b128 runs at
+// full rate (256 B/clk) only if the swizzle suits the fragment shape: 2 for the 32-row fragments of
+// the 32x32x16 MFMA (lane l: row l%32, chunk l/32), 1 for the 16-row fragments of the 16x16x32 MFMA
+// (lane l: row l%16, chunk l/16); the other way round, or without swizzle, it runs at half rate
+// (measured with a read-only microbenchmark: 570 against 305 bytes/ns per CU).
+template <int ROWS, int REGION, int NW, int NB_, int SWZ = 2>
 struct OperandKContig {   // global P[row * ld + k]
+    static_assert(SWZ == 1 || SWZ == 2, "swizzle by (row>>1)&3 or (row>>2)&3");
     static constexpr int QL = ROWS / 16 / NW;  // a load covers 16 rows x 64 B
     static constexpr int NB = NB_;             // 32-row blocks per wave tile
     static_assert(QL >= 1, "at least one load per wave and stage");
@@ -205,8 +211,8 @@ struct OperandKContig {   // global P[row * ld + k]
             base[c] = origin + (size_t)(16 * (wave * QL + STRIDE * c)) * ld_bytes;
             lds_dst[c] = lds0 + REGION + (wave * QL + STRIDE * c) * 1024;
         }
-        // lane -> LDS slot (row = lane>>2, slot = lane&3); that slot holds chunk slot ^ ((row>>2)&3)
-        voff[0] = (lane >> 2) * ld_bytes + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+        // lane -> LDS slot (row = lane>>2, slot = lane&3); that slot holds chunk slot ^ ((row>>SWZ)&3)
+        voff[0] = (lane >> 2) * ld_bytes + (((lane & 3) ^ ((lane >> (2 + SWZ)) & 3)) << 4);
         const uint32_t group_bytes = 16 * ld_bytes;
         lds_par = 0;
         step_add = KB * 2 + group_bytes;
@@ -216,15 +222,15 @@ struct OperandKContig {   // global P[row * ld + k]
             step_add = KB * 2 - group_bytes;
         }
         voff[1] = voff[0] + KB * 2;
-        // reader: row = wave_row_base + 32*I + lane%32 ((row>>2)&3 does not depend on I),
+        // reader: row = wave_row_base + 32*I + lane%32 ((row>>SWZ)&3 does not depend on I),
         // chunk = 2*S + lane/32
         const uint32_t row = wave_row_base + (lane & 31);
-        const uint32_t a0 = lds0 + REGION + row * 64 + (((lane >> 5) ^ ((row >> 2) & 3)) << 4);
+        const uint32_t a0 = lds0 + REGION + row * 64 + (((lane >> 5) ^ ((row >> SWZ) & 3)) << 4);
         raddr[0] = a0;
         raddr[1] = a0 ^ 32;
-        // 16x16x32 reader: row = wave_row_base + 16*I + lane%16 ((row>>2)&3 = (lane>>2)&3 for every I),
+        // 16x16x32 reader: row = wave_row_base + 16*I + lane%16 ((row>>SWZ)&3 = (lane>>SWZ)&3 for every I),
         // chunk = lane/16
-        raddr16 = lds0 + REGION + (wave_row_base + (lane & 15)) * 64 + ((((lane >> 4) & 3) ^ ((lane >> 2) & 3)) << 4);
+        raddr16 = lds0 + REGION + (wave_row_base + (lane & 15)) * 64 + ((((lane >> 4) & 3) ^ ((lane >> SWZ) & 3)) << 4);
     }
     // Load number C of the current K-step (PAIR: for pair C of the row groups now served), for the
     // K-step AHEAD past the window, into the stage at stage_off.

@@ -76,8 +76,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     constexpr int NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS, NTAIL = Cfg::NTAIL;
     constexpr uint32_t SB = Cfg::STAGE_BYTES, RING = Cfg::RING_BYTES;
-    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, NW, MI / 2>, OperandMNContig<BM, 0, NW, MI / 2>>::type;
-    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, NW, NI / 2>,
+    using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, NW, MI / 2, 1>, OperandMNContig<BM, 0, NW, MI / 2>>::type;
+    using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, NW, NI / 2, 1>,
                                           OperandMNContig<BN, BM * KB * 2, NW, NI / 2>>::type;
     constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
     constexpr int NM = MI * NI;                                // MFMAs per K-step
