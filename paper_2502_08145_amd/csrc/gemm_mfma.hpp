@@ -281,7 +281,14 @@ struct OperandKContig {   // global P[row * ld + k]
     }
 };
 
-template <int ROWS, int REGION, int NW, int NB_>
+// TR16: layout for the 16x16x32 fragments.  A transposing read serves its four 16-lane groups (k
+// blocks of 8) two at a time, provided the two groups of a pair fall into different halves of the
+// 64 banks and the four k-rows of a group into one contiguous 128 bytes; with the 32x32x16 layout
+// (chunks swizzled by 4*(k&3)) every group lands on the same banks and the read runs at half rate
+// (measured with a read-only microbenchmark: 296 against 520 bytes/ns per CU).  So chunk c of k-row
+// k sits at position c ^ 2*(k&3) ^ 8*((k>>3)&1).  The swizzle now touches the chunk bits that
+// number a wave's 16-row blocks, so every block has an address register of its own.
+template <int ROWS, int REGION, int NW, int NB_, bool TR16 = false>
 struct OperandMNContig {   // global P[k * ld + row]
     static constexpr int ROWB = ROWS * 2;              // bytes per k-row in LDS
     static constexpr int KR = 1024 / ROWB;             // k-rows per load: 2 (256 rows) or 4 (128 rows)
@@ -298,7 +305,8 @@ struct OperandMNContig {   // global P[k * ld + row]
     uint32_t kstep_bytes;
     uint32_t lds_dst[QL];
     uint32_t raddr[NB];        // [block]: read address in stage 0 for substep 0, first four k
-    uint32_t raddr16[NB];      // [pair of 16-row blocks]: the same for the 16x16x32 fragments
+    static constexpr int NA16 = TR16 ? 2 * NB : NB;
+    uint32_t raddr16[NA16];    // 16x16x32 fragments: [pair of 16-row blocks], TR16: [16-row block]
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base, bool /*first_step_odd*/) {
@@ -314,8 +322,16 @@ struct OperandMNContig {   // global P[k * ld + row]
         // (wave*QL is even).
         const uint32_t kr = lane / CPR, pos = lane % CPR;
         const uint32_t k3_even = kr, k3_odd = (KR == 2) ? 2 + kr : kr;
-        voff[0] = kr * ld_bytes + ((pos ^ (4 * k3_even)) << 4);
-        voff[1] = kr * ld_bytes + ((pos ^ (4 * k3_odd)) << 4);
+        if constexpr (TR16) {
+            // (k>>3)&1 is the same for all loads of a wave: k = KR*(wave*QL + c) + kr with KR*QL <= 8
+            static_assert(KR * QL <= 8, "a wave's loads stay inside one block of eight k-rows");
+            const uint32_t kb = ((uint32_t)(KR * QL * wave) >> 3) & 1u;
+            voff[0] = kr * ld_bytes + ((pos ^ (2 * k3_even) ^ (8 * kb)) << 4);
+            voff[1] = kr * ld_bytes + ((pos ^ (2 * k3_odd) ^ (8 * kb)) << 4);
+        } else {
+            voff[0] = kr * ld_bytes + ((pos ^ (4 * k3_even)) << 4);
+            voff[1] = kr * ld_bytes + ((pos ^ (4 * k3_odd)) << 4);
+        }
         kstep_bytes = KB * ld_bytes;
         // reader (transposing read, 16-lane groups): group g = lane/16 covers m-half g&1 and
         // k-half g>>1; lane s of a group addresses k-row (s>>2) and 4 consecutive m at 4*(s&3).
@@ -329,9 +345,14 @@ struct OperandMNContig {   // global P[k * ld + row]
         // block; lane s of a group addresses k-row (s>>2) and 4 consecutive m at 4*(s&3).  Blocks 2p
         // and 2p+1 differ by 32 bytes (chunk bit 1, which neither the swizzle nor a carry touches).
 #pragma unroll
-        for (int p = 0; p < NB; ++p) {
-            const uint32_t m = wave_row_base + p * 32 + 4 * (sl & 3);
-            raddr16[p] = lds0 + REGION + (kq + 8 * g) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
+        for (int p = 0; p < NA16; ++p) {
+            if constexpr (TR16) {
+                const uint32_t m = wave_row_base + p * 16 + 4 * (sl & 3);
+                raddr16[p] = lds0 + REGION + (kq + 8 * g) * ROWB + (((m >> 3) ^ (2 * kq) ^ (8 * (g & 1))) << 4) + (m & 4) * 2;
+            } else {
+                const uint32_t m = wave_row_base + p * 32 + 4 * (sl & 3);
+                raddr16[p] = lds0 + REGION + (kq + 8 * g) * ROWB + (((m >> 3) ^ (4 * kq)) << 4) + (m & 4) * 2;
+            }
         }
     }
     static constexpr bool PAIR = false;   // a load already covers whole cache lines
@@ -354,23 +375,29 @@ struct OperandMNContig {   // global P[k * ld + row]
     using Frag = Frag64x2;
     template <int I, int S>
     __device__ __forceinline__ void read(Frag& f, const Cursor& c) const {
+        static_assert(!TR16, "the 32x32x16 reader goes with the 32x32x16 layout");
         // k = 16*S + 8*(lane/32) + 0..3 and + 4..7
         lds_read64_tr<(16 * S) * ROWB>(f.lo, c.a[I]);
         lds_read64_tr<(16 * S + 4) * ROWB>(f.hi, c.a[I]);
     }
     struct Cursor16 {
-        uint32_t a[NB];
+        uint32_t a[NA16];
     };
     __device__ __forceinline__ Cursor16 cursor16(uint32_t stage_off) const {
         Cursor16 c;
 #pragma unroll
-        for (int p = 0; p < NB; ++p) c.a[p] = raddr16[p] + stage_off;
+        for (int p = 0; p < NA16; ++p) c.a[p] = raddr16[p] + stage_off;
         return c;
     }
     template <int I>
     __device__ __forceinline__ void read16(Frag& f, const Cursor16& c) const {
-        lds_read64_tr<(I & 1) * 32>(f.lo, c.a[I / 2]);
-        lds_read64_tr<(I & 1) * 32 + 4 * ROWB>(f.hi, c.a[I / 2]);
+        if constexpr (TR16) {
+            lds_read64_tr<0>(f.lo, c.a[I]);
+            lds_read64_tr<4 * ROWB>(f.hi, c.a[I]);
+        } else {
+            lds_read64_tr<(I & 1) * 32>(f.lo, c.a[I / 2]);
+            lds_read64_tr<(I & 1) * 32 + 4 * ROWB>(f.hi, c.a[I / 2]);
+        }
     }
 };
 

@@ -76,9 +76,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     constexpr int NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, MI = Cfg::MI, NI = Cfg::NI, NS = Cfg::NS, NTAIL = Cfg::NTAIL;
     constexpr uint32_t SB = Cfg::STAGE_BYTES, RING = Cfg::RING_BYTES;
+    // The full-rate layout of the transposing reads (TR16) pays in the 8-wave kernel when it is B alone
+    // that is read that way (NN: +2-3 %); with both operands MN-contiguous (TN) it measured 2 % slower
+    // than the old one, and so did the 4-wave NN kernels (1-2 %).
     using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, NW, MI / 2, 1>, OperandMNContig<BM, 0, NW, MI / 2>>::type;
     using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, NW, NI / 2, 1>,
-                                          OperandMNContig<BN, BM * KB * 2, NW, NI / 2>>::type;
+                                          OperandMNContig<BN, BM * KB * 2, NW, NI / 2, (A_KC && NW == 8)>>::type;
     constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
     constexpr int NM = MI * NI;                                // MFMAs per K-step
     static_assert(NM % 8 == 0, "the step is cut in quarters and eighths");
