@@ -245,6 +245,10 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     if (var.bm == 0) return true;
     if (!var.fn[layout]) return false;   // a kernel for one layout only
     if (M <= 0 || N <= 0 || K <= 0) return false;
+    // per-lane address offsets are 32 bits: up to 16 rows of a K-contiguous operand, 4 (64-k kernel: 36)
+    // k-rows of an MN-contiguous one, plus the K window of a K-contiguous one
+    constexpr int64_t kMaxTileDim = (int64_t)1 << 24;
+    if (M > kMaxTileDim || N > kMaxTileDim || K > kMaxTileDim) return false;
     if (M % var.bm != 0 || N % var.bn != 0 || K % (var.kstep * var.splits) != 0 || K / var.splits < var.min_k) return false;
     if (var.splits == 1) return true;
     // scratch: one flag and one fp32 tile per (tile, extra K range)

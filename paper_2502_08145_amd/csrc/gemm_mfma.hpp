@@ -300,9 +300,9 @@ struct OperandMNContig {   // global P[k * ld + row]
     struct Cursor {
         uint32_t a[NB];
     };
-    const uint8_t* base[QL];
-    uint32_t voff[2];          // even / odd load index (the k&3 of the rows they carry differs)
-    uint32_t kstep_bytes;
+    const uint8_t* base;       // uniform: k-row 0 of the wave's first load; the K window moves here
+    uint32_t voff[QL];         // per lane and load: k-row inside the wave's share * ld + fetched chunk * 16
+    size_t kstep_bytes;        // uniform: KB k-rows
     uint32_t lds_dst[QL];
     uint32_t raddr[NB];        // [block]: read address in stage 0 for substep 0, first four k
     static constexpr int NA16 = TR16 ? 2 * NB : NB;
@@ -311,28 +311,23 @@ struct OperandMNContig {   // global P[k * ld + row]
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base, bool /*first_step_odd*/) {
         const uint8_t* origin = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * 2;
+        base = origin + (size_t)(KR * QL * wave) * ld_bytes;
 #pragma unroll
-        for (int c = 0; c < QL; ++c) {
-            const int q = wave * QL + c;               // this load carries k-rows KR*q .. KR*q + KR-1
-            base[c] = origin + (size_t)(KR * q) * ld_bytes;
-            lds_dst[c] = lds0 + REGION + q * 1024;
-        }
+        for (int c = 0; c < QL; ++c) lds_dst[c] = lds0 + REGION + (wave * QL + c) * 1024;   // load c carries k-rows KR*(wave*QL + c) ..
         // lane -> (k-row kr of the load, LDS chunk position lane % CPR); that position holds chunk
         // pos ^ 4*(k&3).  k = KR*q + kr: for KR == 4, k&3 = kr; for KR == 2, k&3 = 2*(c&1) + kr
         // (wave*QL is even).
         const uint32_t kr = lane / CPR, pos = lane % CPR;
         const uint32_t k3_even = kr, k3_odd = (KR == 2) ? 2 + kr : kr;
-        if constexpr (TR16) {
-            // (k>>3)&1 is the same for all loads of a wave: k = KR*(wave*QL + c) + kr with KR*QL <= 8
-            static_assert(KR * QL <= 8, "a wave's loads stay inside one block of eight k-rows");
-            const uint32_t kb = ((uint32_t)(KR * QL * wave) >> 3) & 1u;
-            voff[0] = kr * ld_bytes + ((pos ^ (2 * k3_even) ^ (8 * kb)) << 4);
-            voff[1] = kr * ld_bytes + ((pos ^ (2 * k3_odd) ^ (8 * kb)) << 4);
-        } else {
-            voff[0] = kr * ld_bytes + ((pos ^ (4 * k3_even)) << 4);
-            voff[1] = kr * ld_bytes + ((pos ^ (4 * k3_odd)) << 4);
+        static_assert(KR * QL <= 8, "a wave's loads stay inside one block of eight k-rows");
+        const uint32_t kb = ((uint32_t)(KR * QL * wave) >> 3) & 1u;   // (k>>3)&1, the same for all loads of a wave
+#pragma unroll
+        for (int c = 0; c < QL; ++c) {
+            const uint32_t k3 = (c & 1) ? k3_odd : k3_even;
+            const uint32_t swz = TR16 ? (2 * k3) ^ (8 * kb) : 4 * k3;
+            voff[c] = (uint32_t)(KR * c + kr) * ld_bytes + ((pos ^ swz) << 4);
         }
-        kstep_bytes = KB * ld_bytes;
+        kstep_bytes = (size_t)KB * ld_bytes;
         // reader (transposing read, 16-lane groups): group g = lane/16 covers m-half g&1 and
         // k-half g>>1; lane s of a group addresses k-row (s>>2) and 4 consecutive m at 4*(s&3).
         const uint32_t sl = lane & 15, g = lane >> 4, kq = sl >> 2;
@@ -360,12 +355,11 @@ struct OperandMNContig {   // global P[k * ld + row]
     template <int C, int AHEAD>
     __device__ __forceinline__ void issue(uint32_t stage_off) const {
         static_assert(AHEAD == 0, "loaded one K-step at a time");
-        direct_load16(lds_dst[C] + stage_off, base[C], voff[C & 1]);
+        direct_load16(lds_dst[C] + stage_off, base, voff[C]);
     }
-    __device__ __forceinline__ void advance() {
-        voff[0] += kstep_bytes;
-        voff[1] += kstep_bytes;
-    }
+    // One K-step on.  The window moves in the (64-bit, scalar) base pointers, not in the 32-bit
+    // per-lane offsets: a panel of more than 4 GB (K * ld * 2 bytes) would wrap those.
+    __device__ __forceinline__ void advance() { base += kstep_bytes; }
     __device__ __forceinline__ Cursor cursor(uint32_t stage_off) const {
         Cursor c;
 #pragma unroll

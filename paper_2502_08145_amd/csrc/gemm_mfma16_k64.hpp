@@ -94,27 +94,24 @@ struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32
     static constexpr uint32_t HALF = 256 * KB * 2;   // bytes of one 32-k stage
     static_assert(Inner::QL == 4, "four loads per wave and 32-k stage");
     Inner in;
-    uint32_t voff_hi[2];      // the window of the second stage
+    uint32_t voff_hi[4];      // the loads of the second stage: 32 k-rows on
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base) {
         in.init(P, row0, ld_bytes, lane, wave, lds0, wave_row_base, false);
-        voff_hi[0] = in.voff[0] + in.kstep_bytes;
-        voff_hi[1] = in.voff[1] + in.kstep_bytes;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) voff_hi[c] = in.voff[c] + (uint32_t)in.kstep_bytes;   // fits: ld < 2^24
     }
     template <int X>
     __device__ __forceinline__ void issue(uint32_t buf) const {
         constexpr int C = X % 4;
         if constexpr (X < 4)
-            direct_load16(in.lds_dst[C] + buf, in.base[C], in.voff[C & 1]);
+            direct_load16(in.lds_dst[C] + buf, in.base, in.voff[C]);
         else
-            direct_load16(in.lds_dst[C] + buf + HALF, in.base[C], voff_hi[C & 1]);
+            direct_load16(in.lds_dst[C] + buf + HALF, in.base, voff_hi[C]);
     }
     __device__ __forceinline__ void advance() {
-        in.voff[0] += 2 * in.kstep_bytes;
-        in.voff[1] += 2 * in.kstep_bytes;
-        voff_hi[0] += 2 * in.kstep_bytes;
-        voff_hi[1] += 2 * in.kstep_bytes;
+        in.base += 2 * in.kstep_bytes;   // 64-bit: panels may exceed 4 GB
     }
     template <int S>
     __device__ __forceinline__ Cursor cursor(uint32_t buf) const {

@@ -426,6 +426,27 @@ def test_long_k_four_ranges_full_chip_sampled(oracle_mod):
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
+def test_panel_larger_than_4_gib(oracle_mod):
+    """An MN-contiguous operand of 6 GiB (TN: A stored [K, M] with M = 98304, K = 32768): the K window
+    of its direct loads must move in 64-bit pointers (32-bit per-lane offsets would wrap after 21845
+    k-rows and every output element would be wrong).  A is a seeded 1024-row block repeated along
+    k (the wrap lands a third of a row off, so periodic data still shows it); integer data, sampled
+    outputs compared bit for bit."""
+    M, N, K = 98304, 256, 32768
+    block = synth.integer_bf16(synth.BASE_SEED + 730, (1024, M), -4, 4)
+    A = np.tile(block, (K // 1024, 1))                       # [K, M]
+    Bm = synth.integer_bf16(synth.BASE_SEED + 731, (K, N), -4, 4)
+    assert A.shape == (K, M) and A.nbytes > (1 << 32)
+    rng = np.random.default_rng(730)
+    ii = rng.integers(0, M, 96).astype(np.int64)
+    jj = rng.integers(0, N, 96).astype(np.int64)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, "TN", A, Bm, ii, jj))
+    for v in (-1, [B.variant_name(x) for x in range(B.num_variants())].index("mfma16k64_256x256"),
+              [B.variant_name(x) for x in range(B.num_variants())].index("mfma_256x256_w8")):
+        got = run_gpu("bwd_weight", M, N, K, "TN", A, Bm, variant=v)
+        assert np.array_equal(got[ii, jj], want), f"variant {v}"
+
+
 # ------------------------------------------------------------------ operand re-storage (transpose)
 @pytest.mark.parametrize("shape", [(64, 64), (128, 192), (4096, 1024), (2048, 12288), (1, 7), (65, 130),
                                    (257, 31), (64, 72), (1000, 8)])
