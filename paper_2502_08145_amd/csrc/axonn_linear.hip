@@ -125,12 +125,12 @@ struct Variant {
         }                                                                                            \
     }
 
-// the kernel with 64-k LDS stages (4 waves, one barrier per 64 k)
-#define AXONN_TILE_VARIANT_K64(NAME, SPLITS, BASE)                                                   \
+// the kernel with 64-k LDS stages (one barrier per 64 k), 2 x WN waves
+#define AXONN_TILE_VARIANT_K64(NAME, WN, SPLITS, BASE)                                               \
     {                                                                                                \
-        NAME, 256, 256, TileCfgK64::NT, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, SPLITS, BASE, { \
-            gemm_tile_kernel_k64<true, false, (SPLITS > 1)>, gemm_tile_kernel_k64<true, true, (SPLITS > 1)>, \
-                gemm_tile_kernel_k64<false, false, (SPLITS > 1)>                                     \
+        NAME, 256, 256, 128 * WN, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, SPLITS, BASE, { \
+            gemm_tile_kernel_k64<WN, true, false, (SPLITS > 1)>, gemm_tile_kernel_k64<WN, true, true, (SPLITS > 1)>, \
+                gemm_tile_kernel_k64<WN, false, false, (SPLITS > 1)>                                 \
         }                                                                                            \
     }
 
@@ -172,11 +172,19 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk7", 256, 256, 2, 4, 7, 9),
     AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk8", 256, 256, 2, 4, 8, 9),
     // 64-k LDS stages
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256", 1, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk2", 2, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk3", 3, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk4", 4, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk8", 8, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256", 2, 1, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk2", 2, 2, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk3", 2, 3, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk4", 2, 4, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk8", 2, 8, 14),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8", 4, 1, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk2", 4, 2, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk3", 4, 3, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk4", 4, 4, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk5", 4, 5, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk6", 4, 6, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk7", 4, 7, 15),
+    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk8", 4, 8, 15),
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
 
@@ -267,13 +275,13 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
 static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
-    static const double eff[3][15] = {
+    static const double eff[3][16] = {
         /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
          *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128,
-         *            the 64-k kernel */
-        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85, 1.11},
-        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72, 1.12},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90, 1.06},
+         *            the 64-k kernel with 4 and 8 waves */
+        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85, 1.11, 1.17},
+        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72, 1.12, 1.13},
+        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90, 1.06, 1.10},
     };
     constexpr double kFixedK = 128.0;
     const Variant& var = g_variants[v];

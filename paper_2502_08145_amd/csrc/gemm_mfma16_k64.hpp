@@ -1,25 +1,26 @@
-// The tile kernel with LDS stages of 64 k, four waves and one barrier per 64 k.
+// The tile kernel with LDS stages of 64 k and one barrier per 64 k, four or eight waves.
 //
 // Why a kernel of its own.  In gemm_tile_kernel16 a K-contiguous operand is staged 32 k at a time:
 // a row of a stage is 64 bytes, half a cache line, so every direct load asks the L1 for sixteen
-// half lines, and the 8-wave layout reads every LDS byte three times.  Here:
+// half lines, and there is a barrier every 32 k.  Here:
 //
 //  * a K-contiguous panel is staged 64 k at a time: an LDS row is one whole 128-byte line (row r,
 //    the eight 16-byte chunks XOR-swizzled by (r>>1)&7: ds_read_b128 of sixteen consecutive rows
 //    then touches every bank once), a direct load fetches 8 rows x 128 B: eight full-line requests
 //    instead of sixteen half-line ones.  An MN-contiguous panel is two 32-k stages of
 //    OperandMNContig side by side;
-//  * two buffers of (256 + 256) x 64 k = 64 KB each; 4 waves (2 x 2), wave tile 128 x 128:
-//    every LDS byte is read twice, not three times;
-//  * ONE barrier per 64 k.  An iteration is two sub-steps of 32 k (64 MFMAs per wave each).  During
-//    sub-step 0 of iteration i the fragments of its sub-step 1 are read; during sub-step 1, after
-//    the barrier, the fragments of iteration i+1 (other buffer), and the direct loads of iteration
-//    i+2 go out into the buffer that iteration i has just finished with.  At the barrier every
-//    load issued so far must have landed (vmcnt(0)): those of iteration i+1, issued one iteration
-//    earlier, i.e. a lead of almost two sub-steps.
+//  * two buffers of (256 + 256) x 64 k = 64 KB each; 2 x 2 waves (wave tile 128 x 128: every LDS
+//    byte is read twice, not three times) or 2 x 4 waves (128 x 64, two waves per SIMD);
+//  * ONE barrier per 64 k.  An iteration is two sub-steps of 32 k.  During sub-step 0 of iteration i
+//    the fragments of its sub-step 1 are read; during sub-step 1, after the barrier, the fragments
+//    of iteration i+1 (other buffer), and the direct loads of iteration i+2 go out into the buffer
+//    that iteration i has just finished with.  At the barrier every load issued so far must have
+//    landed (vmcnt(0)): those of iteration i+1, issued one iteration earlier, i.e. a lead of
+//    almost two sub-steps.
 //
-// It pays where both operands are K-contiguous (NT: 5-8 % faster than the 8-wave kernel); for NN it
-// ties and for TN it loses 5 %, so the selection uses it for NT.  Fragments, MFMA order
+// Measured: with eight waves it is the fastest kernel for NN and NT (3-4 % over the 32-k kernel in
+// the benchmark step, more for the split-K forms); with four waves it wins only for NT without
+// split-K, by a hair; TN ties or loses, so TN stays with gemm_tile_kernel16.  Fragments, MFMA order
 // (mfma(Bfrag, Afrag)), accumulator layout, split-K exchange, epilogue and the XCD-aware tile order
 // are those of gemm_tile_kernel16.
 #pragma once
@@ -40,14 +41,15 @@ struct TileCfgK64 {
 //   advance()            window one iteration (64 k) on
 //   cursor(S, buf)       read addresses for sub-step S of that buffer
 //   read<I>(frag, cur)   fragment of 16-row block I
-template <int REGION>
+template <int REGION, int NW>
 struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks swizzled by (row>>1)&7
+    static constexpr int QL = 32 / NW;   // loads per wave and iteration: row groups QL*wave .. (8 rows each)
     using Frag = Frag128;
     struct Cursor {
         uint32_t a;
     };
-    const uint8_t* base[8];   // uniform: row group 8*wave + c (8 rows each), k = 0
-    uint32_t lds_dst;         // uniform: destination of group 8*wave inside buffer 0
+    const uint8_t* base[QL];  // uniform: row group QL*wave + c, k = 0
+    uint32_t lds_dst;         // uniform: destination of group QL*wave inside buffer 0
     uint32_t voff[2];         // per lane, [group parity]: row-in-group * ld + fetched chunk * 16 + window
     uint32_t raddr[2];        // [sub-step]: read address of block 0 in buffer 0
 
@@ -57,10 +59,11 @@ struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks 
     // block I is an immediate offset of I * 2048.
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base) {
+        static_assert(QL % 2 == 0, "a wave's first row group is an even one");
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
-            base[c] = reinterpret_cast<const uint8_t*>(P) + (size_t)(row0 + 8 * (8 * wave + c)) * ld_bytes;
-        lds_dst = lds0 + REGION + (uint32_t)(8 * wave) * 1024u;
+        for (int c = 0; c < QL; ++c)
+            base[c] = reinterpret_cast<const uint8_t*>(P) + (size_t)(row0 + 8 * (QL * wave + c)) * ld_bytes;
+        lds_dst = lds0 + REGION + (uint32_t)(QL * wave) * 1024u;
         const uint32_t r16 = lane & 15, quad = lane >> 4;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -86,26 +89,27 @@ struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks 
     }
 };
 
-template <int REGION>
+template <int REGION, int NW, int NB>
 struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32-k stages of OperandMNContig
-    using Inner = OperandMNContig<256, REGION, 4, 4>;
+    using Inner = OperandMNContig<256, REGION, NW, NB>;
+    static constexpr int QH = Inner::QL;   // loads per wave and 32-k stage
+    static constexpr int QL = 2 * QH;
     using Frag = typename Inner::Frag;
     using Cursor = typename Inner::Cursor16;
     static constexpr uint32_t HALF = 256 * KB * 2;   // bytes of one 32-k stage
-    static_assert(Inner::QL == 4, "four loads per wave and 32-k stage");
     Inner in;
-    uint32_t voff_hi[4];      // the loads of the second stage: 32 k-rows on
+    uint32_t voff_hi[QH];     // the loads of the second stage: 32 k-rows on
 
     __device__ __forceinline__ void init(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int lane, int wave,
                                          uint32_t lds0, int wave_row_base) {
         in.init(P, row0, ld_bytes, lane, wave, lds0, wave_row_base, false);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) voff_hi[c] = in.voff[c] + (uint32_t)in.kstep_bytes;   // fits: ld < 2^24
+        for (int c = 0; c < QH; ++c) voff_hi[c] = in.voff[c] + (uint32_t)in.kstep_bytes;   // fits: ld < 2^24
     }
     template <int X>
     __device__ __forceinline__ void issue(uint32_t buf) const {
-        constexpr int C = X % 4;
-        if constexpr (X < 4)
+        constexpr int C = X % QH;
+        if constexpr (X < QH)
             direct_load16(in.lds_dst[C] + buf, in.base, in.voff[C]);
         else
             direct_load16(in.lds_dst[C] + buf + HALF, in.base, voff_hi[C]);
@@ -124,15 +128,17 @@ struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32
 };
 
 // Requires M % 256 == 0, N % 256 == 0, K % 64 == 0, K >= 128 (per K range when split).
-template <bool A_KC, bool B_KC, bool SPLITK>
-__global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
+template <int WN, bool A_KC, bool B_KC, bool SPLITK>
+__global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n, int group_m, SplitK sk) {
     using Cfg = TileCfgK64;
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, NW = 4, WN = 2;
-    constexpr int TM = 128, TN = 128, MI = 8, NI = 8, NM = MI * NI;
+    static_assert(WN == 2 || WN == 4, "2 x 2 or 2 x 4 waves");
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, NW = 2 * WN;
+    constexpr int TM = BM / 2, TN = BN / WN, MI = TM / 16, NI = TN / 16, NM = MI * NI;
     constexpr uint32_t BUF = Cfg::BUF_BYTES, REGION_B = Cfg::A_BYTES;
-    constexpr int QL = 8;   // direct loads per wave, operand and iteration: 8 row groups of 8 rows
+    constexpr int QL = 32 / NW;   // direct loads per wave, operand and iteration
+    constexpr int NLD = 2 * QL, NRD = MI + NI;   // ... and loads / fragment reads per wave and iteration / sub-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int t = threadIdx.x;
@@ -174,8 +180,9 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     const int64_t k0 = (int64_t)krange * ktotal;
 
     // ---- operands ------------------------------------------------------------------------------------
-    using OpA = typename std::conditional<A_KC, OperandK64KContig<0>, OperandK64MNContig<0>>::type;
-    using OpB = typename std::conditional<B_KC, OperandK64KContig<REGION_B>, OperandK64MNContig<REGION_B>>::type;
+    using OpA = typename std::conditional<A_KC, OperandK64KContig<0, NW>, OperandK64MNContig<0, NW, MI / 2>>::type;
+    using OpB = typename std::conditional<B_KC, OperandK64KContig<REGION_B, NW>, OperandK64MNContig<REGION_B, NW, NI / 2>>::type;
+    static_assert(OpA::QL == QL && OpB::QL == QL, "loads per wave");
     const uint32_t lds0 = lds_address(smem);
     OpA opa;
     OpB opb;
@@ -219,27 +226,18 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     };
     auto wait_fragments = [&](auto s_c) __attribute__((always_inline)) {
         constexpr int S = decltype(s_c)::value;
-        tie_to_lds_wait<4>(&fa[S][0]);
-        tie_to_lds_wait<4>(&fa[S][4]);
-        tie_to_lds_wait<4>(&fb[S][0]);
-        tie_to_lds_wait<4>(&fb[S][4]);
+        static_for<MI / 4>([&](auto d) __attribute__((always_inline)) { tie_to_lds_wait<4>(&fa[S][4 * decltype(d)::value]); });
+        static_for<NI / 4>([&](auto d) __attribute__((always_inline)) { tie_to_lds_wait<4>(&fb[S][4 * decltype(d)::value]); });
     };
-    // cluster Q of NC: its share of the sixteen fragment reads of a sub-step into register buffer S
-    // (A blocks, then B), and of the sixteen direct loads of an iteration
-#ifndef AXONN_K64_NC
-#define AXONN_K64_NC 4
-#endif
-#ifndef AXONN_K64_PB
-#define AXONN_K64_PB 8
-#endif
-#ifndef AXONN_K64_LAST
-#define AXONN_K64_LAST 47
-#endif
-    constexpr int NC = AXONN_K64_NC, PER = 16 / NC;
+    // cluster Q of NC = 4: its share of the fragment reads of a sub-step into register buffer S (A
+    // blocks, then B), and of the direct loads of an iteration
+    constexpr int NC = 4, RPC = NRD / NC, LPC = NLD / NC;
+    constexpr int PB = NM / 8;                          // MFMAs before the barrier and the first cluster
+    constexpr int DP = (3 * NM / 4 - PB) / (NC - 1);    // ... between clusters
     auto read_cluster = [&](auto q_c, auto s_c, const typename OpA::Cursor& ca, const typename OpB::Cursor& cb) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
-        static_for<PER>([&](auto d) __attribute__((always_inline)) {
-            constexpr int X = PER * Q + decltype(d)::value;
+        static_for<RPC>([&](auto d) __attribute__((always_inline)) {
+            constexpr int X = RPC * Q + decltype(d)::value;
             if constexpr (X < MI)
                 opa.template read<X>(fa[S][X], ca);
             else
@@ -248,15 +246,15 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
     };
     auto load_cluster = [&](auto q_c, uint32_t buf) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value;
-        static_for<PER>([&](auto d) __attribute__((always_inline)) { issue(Int<PER * Q + decltype(d)::value>{}, buf); });
+        static_for<LPC>([&](auto d) __attribute__((always_inline)) { issue(Int<LPC * Q + decltype(d)::value>{}, buf); });
     };
 
     // ---- prologue: iterations 0 and 1 into buffers 0 and 1 -----------------------------------------
-    static_for<16>([&](auto x) __attribute__((always_inline)) { issue(x, 0u); });
+    static_for<NLD>([&](auto x) __attribute__((always_inline)) { issue(x, 0u); });
     advance_window();
-    static_for<16>([&](auto x) __attribute__((always_inline)) { issue(x, BUF); });
+    static_for<NLD>([&](auto x) __attribute__((always_inline)) { issue(x, BUF); });
     advance_window();
-    wait_vmcnt<16>();   // iteration 0 has landed
+    wait_vmcnt<NLD>();   // iteration 0 has landed
     __builtin_amdgcn_s_barrier();
     AXONN_FENCE();
 
@@ -270,7 +268,6 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel_k64(
         constexpr int S = decltype(s_c)::value;
         constexpr bool READ = decltype(read_c)::value, LOAD = decltype(load_c)::value;
         static_assert(!LOAD || (S == 1 && READ), "loads go out in sub-step 1 of an iteration that has a successor");
-        constexpr int PB = AXONN_K64_PB, DP = (AXONN_K64_LAST - PB) / (NC - 1);
         wait_fragments(s_c);
         AXONN_FENCE();
         mfma_range(s_c, Int<0>{}, Int<PB>{});

@@ -169,7 +169,7 @@ def test_split_k_long_k_one_range_per_xcd_pair(oracle_mod, layout, shape):
             got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
             assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
         ran += 1
-    assert ran == 5
+    assert ran == 6
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
