@@ -26,11 +26,11 @@ def short(name: str) -> str:
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
         waves = "_w8" if int(wm) * int(wn) == 8 else ""
         return f"mfma{k16 or ''}_{bm}x{bn}{waves}{'_sk' if split == 'true' else ''}/{lay}"
-    m = re.search(r"gemm_tile_kernel_k64<(true|false), (true|false), (true|false)>", name)
+    m = re.search(r"gemm_tile_kernel_k64<(\d+), (true|false), (true|false), (true|false)>", name)
     if m:
-        akc, bkc, split = m.groups()
+        wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
-        return f"mfma16k64_256x256{'_sk' if split == 'true' else ''}/{lay}"
+        return f"mfma16k64_256x256{'_w8' if wn == '4' else ''}{'_sk' if split == 'true' else ''}/{lay}"
     if "copy_probe_kernel" in name:
         return "copy_probe"
     if "gemm_naive_kernel" in name:
