@@ -412,6 +412,57 @@ struct SplitK {
 constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~3 us per probe
 constexpr int kSplitRangePerXcdK = 32768;        // four K ranges: from this K on, one range per pair of XCDs
 
+// Workgroup -> output tile and K range.  The hardware hands workgroup b to XCD b % 8, in order of b
+// on each XCD, and every XCD has a private L2: ids are remapped so that an XCD works on a contiguous
+// chunk of the tile sequence, and tiles are then grouped `group_m` along m, which makes the tiles
+// running side by side behind one L2 a compact patch of the output (they share operand panels).
+// Split-K: the workgroups of a tile sit on the same XCD, last K range first (writers get the lower
+// ids) -- except with four ranges of a large tile at long K, where XCDs 0-1 take the last K range,
+// ..., XCDs 6-7 range 0, each a contiguous chunk of the tiles, so the 32 workgroups that share an L2
+// read the same K slices (with all four ranges of a tile on one XCD they would share a quarter as
+// much; measured 17-20 % faster at K = 65536 for NN and NT).  The readers then sit on two XCDs only,
+// which makes the exchange slower by some 10 us: not for short K.  Writers keep the lower ids there
+// too (same pid >> 3, lower XCD).
+struct TileWork {
+    int tile_id;          // index into the tile sequence (= split-K slot index within a range)
+    int tile_m, tile_n;
+    int krange, ktotal;   // this workgroup's K range and its length
+};
+template <bool SPLITK, bool LARGE_TILE>
+__device__ __forceinline__ TileWork map_workgroup(int pid, int nwg, int K, int tiles_m, int tiles_n, int group_m,
+                                                  const SplitK& sk) {
+    TileWork w;
+    w.krange = 0;
+    w.ktotal = K;
+    if constexpr (SPLITK) {
+        const int splits = sk.splits, tiles = tiles_m * tiles_n;
+        if (LARGE_TILE && splits == 4 && (nwg & 7) == 0 && K >= kSplitRangePerXcdK) {
+            const int x = pid & 7, q = pid >> 3, tp = tiles >> 1;
+            w.krange = 3 - (x >> 1);
+            pid = (x & 1) * tp + q;
+        } else if (nwg % (8 * splits) == 0) {
+            const int tp = (nwg >> 3) / splits, li = pid >> 3;
+            w.krange = splits - 1 - li / tp;
+            pid = (pid & 7) * tp + li % tp;
+        } else {
+            w.krange = splits - 1 - pid / tiles;
+            pid = pid % tiles;
+        }
+        w.ktotal = K / splits;
+    } else {
+        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+    }
+    w.tile_id = pid;
+    const int group_sz = group_m * tiles_n;
+    const int group = pid / group_sz;
+    const int first_m = group * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
+    const int in_group = pid - group * group_sz;
+    w.tile_m = first_m + in_group % gm;
+    w.tile_n = in_group / gm;
+    return w;
+}
+
 // ------------------------------------------------------------------------------------------------
 // NS = number of LDS stages: as many as fit (160 KB per CU; the 128x128 tile takes 80 KB so that
 // two workgroups share a CU).  WM x WN waves: 2 x 2 (one wave per SIMD) or 2 x 4 (two).
@@ -478,46 +529,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- workgroup -> output tile: XCD-contiguous, then grouped along m ------------------------
-    // (the hardware hands workgroup b to XCD b % 8, in order of b on each XCD)
-    int pid = blockIdx.x;
-    const int nwg = gridDim.x;
-    int krange = 0, ktotal = K;   // this workgroup's K range index and length
-    if constexpr (SPLITK) {
-        const int splits = sk.splits, tiles = tiles_m * tiles_n;
-        if (BM * BN == 256 * 256 && splits == 4 && (nwg & 7) == 0 && K >= kSplitRangePerXcdK) {
-            // Long K: XCDs 0-1 take the last K range, ..., XCDs 6-7 range 0, each a contiguous chunk
-            // of the tiles, so the 32 workgroups that share an L2 read the same K slices (with
-            // all four ranges of a tile on one XCD they would share a quarter as much; measured
-            // 17-20 % faster at K = 65536 for NN and NT).  The readers then sit on two XCDs only,
-            // which makes the exchange slower by some 10 us: not for short K.  Writers keep the
-            // lower workgroup ids (same pid >> 3, lower XCD).
-            const int x = pid & 7, q = pid >> 3, tp = tiles >> 1;
-            krange = 3 - (x >> 1);
-            pid = (x & 1) * tp + q;
-        } else
-        if (nwg % (8 * splits) == 0) {
-            // XCD x owns tiles [x*tp, (x+1)*tp): first the workgroups of the last K range, ... last
-            // those of range 0
-            const int tp = (nwg >> 3) / splits, li = pid >> 3;
-            krange = splits - 1 - li / tp;
-            pid = (pid & 7) * tp + li % tp;
-        } else {
-            krange = splits - 1 - pid / tiles;
-            pid = pid % tiles;
-        }
-        ktotal = K / splits;
-    } else {
-        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
-    }
-    const int tile_id = pid;
-    const int group_sz = group_m * tiles_n;
-    const int group = pid / group_sz;
-    const int first_m = group * group_m;
-    const int gm = min(tiles_m - first_m, group_m);
-    const int in_group = pid - group * group_sz;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
+    // ---- workgroup -> output tile and K range ------------------------------------------------
+    const TileWork work = map_workgroup<SPLITK, BM * BN == 256 * 256>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
+    const int tile_id = work.tile_id, tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange, ktotal = work.ktotal;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
     const uint32_t lds0 = lds_address(smem);
@@ -590,7 +604,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
     // issues the same NL loads, and K-step u is complete once the loads of step u-NS+1 (plain) or
     // u-NS+2 (any operand paired) are.  KIND: 2 = all of the above, 1 = K-step t+NS-1 no longer
     // exists (a paired operand still fetches its half of t+NS-2), 0 = nothing.
-    constexpr bool ANY_PAIR = OpA::PAIR || OpB::PAIR;
     auto issue_loads = [&](auto op_c, auto kind_c, auto half_c, uint32_t st_near, uint32_t st_far) __attribute__((always_inline)) {
         constexpr bool IS_A = decltype(op_c)::value == 0;
         constexpr int KIND = decltype(kind_c)::value, H = decltype(half_c)::value;
@@ -703,7 +716,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
         st_next = next_stage(st_next);
     };
     using Yes = std::true_type;
-    using No = std::false_type;
 
     // After KT-NS+1 full steps come the steps that fetch less: one of kind 1 if an operand is
     // paired (K-step KT-1 still lacks that operand's other half), then kind 0 to the end.

@@ -67,6 +67,95 @@ struct LoadPlan16 {
     static constexpr int PROLOGUE_VM = (NS - (ANY_PAIR ? 2 : 1)) * NL;   // K-step 0 has landed
 };
 
+// ---- shared by the kernels whose accumulators are 16x16 blocks: acc[i][j][e] = C[m = i*16 + l%16]
+// [n = j*16 + 4*(l/16) + e] of the wave tile ------------------------------------------------------------
+
+// Split-K exchange (see SplitK).  Slot element ((wave*MI + i)*NI + j)*64 + lane, 16 bytes each.  Returns
+// true for the workgroups of K ranges 1.. (they are done); the range-0 workgroup returns false with
+// the other ranges added to its accumulators, in range order.
+template <int BM, int BN, int MI, int NI>
+__device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const SplitK& sk, int krange, int tile_id,
+                                                   int tiles, int wave, int lane, int t) {
+    const size_t in_slot = (size_t)wave * (MI * NI * 64) + lane;
+    if (krange != 0) {
+        const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
+        f32x4* dst = reinterpret_cast<f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) dst[(i * NI + j) * 64] = acc[i][j];
+        // Cache maintenance is dear on a chip of eight private L2s (a device-scope release writes the
+        // L2 back, an acquire invalidates it), so each workgroup does it once: the barrier orders
+        // every thread's stores before thread 0's release, and thread 0's acquire before every
+        // thread's loads.
+        __syncthreads();
+        if (t == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __hip_atomic_store(&sk.flags[slot], sk.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return true;
+    }
+    for (int r = 1; r < sk.splits; ++r) {
+        const size_t slot = (size_t)(r - 1) * tiles + tile_id;
+        if (t == 0) {
+            uint32_t probes = 0;
+            while (__hip_atomic_load(&sk.flags[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != sk.epoch) {
+                if (++probes > kSplitSpinLimit) {
+                    atomicAdd(sk.timeouts, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(32);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // no stale cached copy of the slot
+        }
+        __syncthreads();
+        const f32x4* src = reinterpret_cast<const f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            f32x4 v[NI];   // a row of blocks at a time: all its loads are in flight together
+#pragma unroll
+            for (int j = 0; j < NI; ++j) v[j] = __builtin_nontemporal_load(src + (i * NI + j) * 64);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) acc[i][j] += v[j];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    return false;
+}
+
+// Epilogue: fp32 -> bf16 (round to nearest even, once), transposed through this wave's private LDS
+// region (TM x TN bf16 at smem + wave * TM*TN*2; all waves must be done with the operand buffers),
+// 16-byte coalesced stores.  `pc` points at the wave tile's first element in C.
+template <int TM, int TN, int MI, int NI>
+__device__ __forceinline__ void store_tile16(f32x4 (&acc)[MI][NI], uint8_t* smem, uint16_t* pc, int ldc, int wave, int lane) {
+    constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile (8 or 16)
+    constexpr uint32_t CMASK = CPR - 1;
+    const uint32_t quad = lane >> 4, r16 = lane & 15;
+    uint8_t* epi = smem + wave * (TM * TN * 2);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const uint32_t row = i * 16 + r16;
+            const uint32_t chunk = j * 2 + (quad >> 1);
+            u32x2 v;
+            v[0] = pack2_bf16(acc[i][j][0], acc[i][j][1]);
+            v[1] = pack2_bf16(acc[i][j][2], acc[i][j][3]);
+            *reinterpret_cast<u32x2*>(epi + row * (TN * 2) + ((chunk ^ (row & CMASK)) << 4) + (quad & 1) * 8) = v;
+        }
+        __builtin_amdgcn_sched_barrier(0);   // convert block row by block row: keeps register pressure low
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < (TM * CPR) / 64; ++it) {
+        const uint32_t idx = it * 64 + lane;
+        const uint32_t row = idx / CPR, ch = idx % CPR;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
+        *reinterpret_cast<u32x4*>(pc + (int64_t)row * ldc + ch * 8) = v;
+    }
+}
+
 // Requires M % BM == 0, N % BN == 0, K % 64 == 0, K >= TileCfg16::MIN_K (per K range when split).
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
@@ -82,7 +171,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     using OpA = typename std::conditional<A_KC, OperandKContig<BM, 0, NW, MI / 2, 1>, OperandMNContig<BM, 0, NW, MI / 2>>::type;
     using OpB = typename std::conditional<B_KC, OperandKContig<BN, BM * KB * 2, NW, NI / 2, 1>,
                                           OperandMNContig<BN, BM * KB * 2, NW, NI / 2, (A_KC && NW == 8)>>::type;
-    constexpr int QA = OpA::QL, QB = OpB::QL, NL = QA + QB;   // direct loads per wave per stage
+    constexpr int QA = OpA::QL, QB = OpB::QL;                  // direct loads per wave per stage
     constexpr int NM = MI * NI;                                // MFMAs per K-step
     static_assert(NM % 8 == 0, "the step is cut in quarters and eighths");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -92,43 +181,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- workgroup -> output tile and K range (as in gemm_tile_kernel) -------------------------
-    int pid = blockIdx.x;
-    const int nwg = gridDim.x;
-    int krange = 0, ktotal = K;
-    if constexpr (SPLITK) {
-        const int splits = sk.splits, tiles = tiles_m * tiles_n;
-        if (BM * BN == 256 * 256 && splits == 4 && (nwg & 7) == 0 && K >= kSplitRangePerXcdK) {
-            // Long K: XCDs 0-1 take the last K range, ..., XCDs 6-7 range 0, each a contiguous chunk
-            // of the tiles, so the 32 workgroups that share an L2 read the same K slices (with
-            // all four ranges of a tile on one XCD they would share a quarter as much; measured
-            // 17-20 % faster at K = 65536 for NN and NT).  The readers then sit on two XCDs only,
-            // which makes the exchange slower by some 10 us: not for short K.  Writers keep the
-            // lower workgroup ids (same pid >> 3, lower XCD).
-            const int x = pid & 7, q = pid >> 3, tp = tiles >> 1;
-            krange = 3 - (x >> 1);
-            pid = (x & 1) * tp + q;
-        } else
-        if (nwg % (8 * splits) == 0) {
-            const int tp = (nwg >> 3) / splits, li = pid >> 3;
-            krange = splits - 1 - li / tp;
-            pid = (pid & 7) * tp + li % tp;
-        } else {
-            krange = splits - 1 - pid / tiles;
-            pid = pid % tiles;
-        }
-        ktotal = K / splits;
-    } else {
-        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
-    }
-    const int tile_id = pid;
-    const int group_sz = group_m * tiles_n;
-    const int group = pid / group_sz;
-    const int first_m = group * group_m;
-    const int gm = min(tiles_m - first_m, group_m);
-    const int in_group = pid - group * group_sz;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
+    // ---- workgroup -> output tile and K range ------------------------------------------------
+    const TileWork work = map_workgroup<SPLITK, BM * BN == 256 * 256>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
+    const int tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange, ktotal = work.ktotal;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
     const uint32_t lds0 = lds_address(smem);
@@ -188,7 +243,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     // Direct loads (see gemm_tile_kernel): during K-step t, after its barrier, a plain operand fetches
     // K-step t+NS into the stage just released ("far"), a paired operand half its row groups for
     // K-steps t+NS-1 and t+NS into the stages "near" (released one step earlier) and "far".
-    constexpr bool ANY_PAIR = OpA::PAIR || OpB::PAIR;
     auto issue_loads = [&](auto op_c, auto kind_c, auto half_c, uint32_t st_near, uint32_t st_far) __attribute__((always_inline)) {
         constexpr bool IS_A = decltype(op_c)::value == 0;
         constexpr int KIND = decltype(kind_c)::value, H = decltype(half_c)::value;
@@ -317,81 +371,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
     }
     __syncthreads();   // every wave is done with the ring before the epilogue reuses LDS
 
-    // ---- split-K exchange: slot element ((wave*MI + i)*NI + j)*64 + lane, 16 bytes each -------------
     if constexpr (SPLITK) {
-        const int tiles = tiles_m * tiles_n;
-        const size_t in_slot = (size_t)wave * (MI * NI * 64) + lane;
-        if (krange != 0) {
-            const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
-            f32x4* dst = reinterpret_cast<f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) dst[(i * NI + j) * 64] = acc[i][j];
-            // one device-scope release per workgroup (see gemm_tile_kernel)
-            __syncthreads();
-            if (t == 0) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                __hip_atomic_store(&sk.flags[slot], sk.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            return;
-        }
-        for (int r = 1; r < sk.splits; ++r) {
-            const size_t slot = (size_t)(r - 1) * tiles + tile_id;
-            if (t == 0) {
-                uint32_t probes = 0;
-                while (__hip_atomic_load(&sk.flags[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != sk.epoch) {
-                    if (++probes > kSplitSpinLimit) {
-                        atomicAdd(sk.timeouts, 1u);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(32);
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            }
-            __syncthreads();
-            const f32x4* src = reinterpret_cast<const f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                f32x4 v[NI];
-#pragma unroll
-                for (int j = 0; j < NI; ++j) v[j] = __builtin_nontemporal_load(src + (i * NI + j) * 64);
-                AXONN_FENCE();
-#pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j] += v[j];
-                AXONN_FENCE();
-            }
-        }
+        if (split_k_exchange16<BM, BN, MI, NI>(acc, sk, krange, work.tile_id, tiles_m * tiles_n, wave, lane, t)) return;
     }
-
-    // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
-    // acc[i][j][e] = C[m = i*16 + l%16][n = j*16 + 4*(l/16) + e]
-    constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile (8 or 16)
-    constexpr uint32_t CMASK = CPR - 1;
-    const uint32_t quad = lane >> 4, r16 = lane & 15;
-    uint8_t* epi = smem + wave * (TM * TN * 2);
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const uint32_t row = i * 16 + r16;
-            const uint32_t chunk = j * 2 + (quad >> 1);
-            u32x2 v;
-            v[0] = pack2_bf16(acc[i][j][0], acc[i][j][1]);
-            v[1] = pack2_bf16(acc[i][j][2], acc[i][j][3]);
-            *reinterpret_cast<u32x2*>(epi + row * (TN * 2) + ((chunk ^ (row & CMASK)) << 4) + (quad & 1) * 8) = v;
-        }
-        AXONN_FENCE();   // convert block row by block row: keeps register pressure low
-    }
-    __syncthreads();
-    uint16_t* pc = C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN;
-#pragma unroll
-    for (int it = 0; it < (TM * CPR) / 64; ++it) {
-        const uint32_t idx = it * 64 + lane;
-        const uint32_t row = idx / CPR, ch = idx % CPR;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
-        *reinterpret_cast<u32x4*>(pc + (int64_t)row * ldc + ch * 8) = v;
-    }
+    store_tile16<TM, TN, MI, NI>(acc, smem, C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN, ldc, wave, lane);
 #undef AXONN_FENCE
 }
 

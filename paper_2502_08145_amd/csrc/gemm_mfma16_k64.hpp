@@ -146,36 +146,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- workgroup -> output tile and K range (as in gemm_tile_kernel) -------------------------
-    int pid = blockIdx.x;
-    const int nwg = gridDim.x;
-    int krange = 0, ktotal = K;
-    if constexpr (SPLITK) {
-        const int splits = sk.splits, tiles = tiles_m * tiles_n;
-        if (splits == 4 && (nwg & 7) == 0 && K >= kSplitRangePerXcdK) {
-            const int x = pid & 7, q = pid >> 3, tp = tiles >> 1;
-            krange = 3 - (x >> 1);
-            pid = (x & 1) * tp + q;
-        } else if (nwg % (8 * splits) == 0) {
-            const int tp = (nwg >> 3) / splits, li = pid >> 3;
-            krange = splits - 1 - li / tp;
-            pid = (pid & 7) * tp + li % tp;
-        } else {
-            krange = splits - 1 - pid / tiles;
-            pid = pid % tiles;
-        }
-        ktotal = K / splits;
-    } else {
-        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
-    }
-    const int tile_id = pid;
-    const int group_sz = group_m * tiles_n;
-    const int group = pid / group_sz;
-    const int first_m = group * group_m;
-    const int gm = min(tiles_m - first_m, group_m);
-    const int in_group = pid - group * group_sz;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
+    // ---- workgroup -> output tile and K range ------------------------------------------------
+    const TileWork work = map_workgroup<SPLITK, true>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
+    const int tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange, ktotal = work.ktotal;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int64_t k0 = (int64_t)krange * ktotal;
 
@@ -313,81 +286,10 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     substep(Int<1>{}, No{}, No{});
     __syncthreads();   // every wave is done with the buffers before the epilogue reuses LDS
 
-    // ---- split-K exchange: slot element ((wave*MI + i)*NI + j)*64 + lane, 16 bytes each -------------
     if constexpr (SPLITK) {
-        const int tiles = tiles_m * tiles_n;
-        const size_t in_slot = (size_t)wave * (MI * NI * 64) + lane;
-        if (krange != 0) {
-            const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
-            f32x4* dst = reinterpret_cast<f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) dst[(i * NI + j) * 64] = acc[i][j];
-            // one device-scope release per workgroup (see gemm_tile_kernel)
-            __syncthreads();
-            if (t == 0) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                __hip_atomic_store(&sk.flags[slot], sk.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            return;
-        }
-        for (int r = 1; r < sk.splits; ++r) {
-            const size_t slot = (size_t)(r - 1) * tiles + tile_id;
-            if (t == 0) {
-                uint32_t probes = 0;
-                while (__hip_atomic_load(&sk.flags[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != sk.epoch) {
-                    if (++probes > kSplitSpinLimit) {
-                        atomicAdd(sk.timeouts, 1u);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(32);
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            }
-            __syncthreads();
-            const f32x4* src = reinterpret_cast<const f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                f32x4 v[NI];
-#pragma unroll
-                for (int j = 0; j < NI; ++j) v[j] = __builtin_nontemporal_load(src + (i * NI + j) * 64);
-                AXONN_FENCE();
-#pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j] += v[j];
-                AXONN_FENCE();
-            }
-        }
+        if (split_k_exchange16<BM, BN, MI, NI>(acc, sk, krange, work.tile_id, tiles_m * tiles_n, wave, lane, t)) return;
     }
-
-    // ---- epilogue: fp32 -> bf16, transpose through this wave's private LDS region --------------
-    // acc[i][j][e] = C[m = i*16 + l%16][n = j*16 + 4*(l/16) + e]
-    constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile
-    const uint32_t r16 = lane & 15, quad = lane >> 4;
-    constexpr uint32_t CMASK = CPR - 1;
-    uint8_t* epi = smem + wave * (TM * TN * 2);
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const uint32_t row = i * 16 + r16;
-            const uint32_t chunk = j * 2 + (quad >> 1);
-            u32x2 v;
-            v[0] = pack2_bf16(acc[i][j][0], acc[i][j][1]);
-            v[1] = pack2_bf16(acc[i][j][2], acc[i][j][3]);
-            *reinterpret_cast<u32x2*>(epi + row * (TN * 2) + ((chunk ^ (row & CMASK)) << 4) + (quad & 1) * 8) = v;
-        }
-        AXONN_FENCE();   // convert block row by block row: keeps register pressure low
-    }
-    __syncthreads();
-    uint16_t* pc = C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN;
-#pragma unroll
-    for (int it = 0; it < (TM * CPR) / 64; ++it) {
-        const uint32_t idx = it * 64 + lane;
-        const uint32_t row = idx / CPR, ch = idx % CPR;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
-        *reinterpret_cast<u32x4*>(pc + (int64_t)row * ldc + ch * 8) = v;
-    }
+    store_tile16<TM, TN, MI, NI>(acc, smem, C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN, ldc, wave, lane);
 #undef AXONN_FENCE
 }
 
