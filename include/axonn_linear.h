@@ -56,8 +56,10 @@
  *   sizes      M, N, K >= 0, each below 2^31, and each operand below 2^40 elements.
  *              M == 0 or N == 0: nothing to do, AXONN_OK.  K == 0: the output is
  *              set to +0.  Any M, N, K is computed correctly; the fast tiled
- *              kernels need M and N to be multiples of 128 and K of 32 (K >= 160), other
- *              shapes take a slower guarded kernel.
+ *              kernels need M and N to be multiples of 128 and K of 32 (K >= 160).  Other
+ *              shapes take a slower guarded MFMA kernel: for the whole product if K does
+ *              not suit the tiled kernels, else only for the last columns and rows beyond
+ *              the whole 128 x 128 tiles.
  *   errors     the return value is AXONN_OK (0) or a negative code below; on an
  *              error nothing has been launched.  No exceptions, no aborts.
  *   threads    callable from any thread; the process-wide state is the kernel
@@ -220,8 +222,9 @@ int axonn_linear_set_split_k(int enable);
 int axonn_linear_split_k_timeouts(uint64_t *count);
 
 /* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any
- * shape; the others are MFMA tile kernels ("_w8": 8 waves, "_sk2"/"_sk4": split-K over 2 or 4
- * workgroups).  Host-only queries: no GPU is touched. */
+ * shape (the library itself uses it for K == 0 only); the last one ("mfma16_edge_128x128") is the
+ * guarded MFMA kernel for any M, N, K >= 1; the others are MFMA tile kernels ("_w8": 8 waves,
+ * "_sk2" ... "_sk8": split-K over that many workgroups).  Host-only queries: no GPU is touched. */
 int axonn_linear_num_variants(void);
 /* Name such as "mfma_256x256"; NULL if `variant` is out of range. */
 const char *axonn_linear_variant_name(int variant);
@@ -235,14 +238,17 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout);
  * into two blocks (the second holds the last rows or the last columns), each with the variant
  * that suits it, e.g. the large tile for the first and split-K for the second.  Block i covers
  * rows row0 .. row0+m-1 and columns col0 .. col0+n-1 of the M x N output; the blocks are
- * disjoint and cover it.  Writes parts[0 .. return value - 1] (HOST memory, caller-owned, room
- * for 2) and returns the number of launches, 1 or 2; negative error code on bad arguments.
- * Pure host logic. */
+ * disjoint and cover it.  A ragged output (M or N not a multiple of 128) whose K suits the tile
+ * kernels is planned over its whole tiles as above, and the last columns and the last rows follow
+ * as up to two blocks of the guarded MFMA kernel.  Writes parts[0 .. return value - 1] (HOST
+ * memory, caller-owned, room for AXONN_MAX_PLAN_PARTS) and returns the number of launches, 1 to
+ * AXONN_MAX_PLAN_PARTS; negative error code on bad arguments.  Pure host logic. */
+#define AXONN_MAX_PLAN_PARTS 4
 typedef struct {
     int variant;
     int64_t m, n, row0, col0;
 } axonn_plan_part_t;
-int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[2]);
+int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[AXONN_MAX_PLAN_PARTS]);
 /* Override the choice for all later calls in this process; -1 restores automatic selection.
  * Returns AXONN_OK or AXONN_ERR_INVALID_ARG.  For tests, tuning and the benchmark. */
 int axonn_linear_force_variant(int variant);

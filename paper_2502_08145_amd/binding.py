@@ -158,13 +158,16 @@ def variant_supports(v: int, M: int, N: int, K: int, layout) -> bool:
     return bool(lib().axonn_linear_variant_supports(int(v), M, N, K, _layout(layout)))
 
 
+MAX_PLAN_PARTS = 4   # AXONN_MAX_PLAN_PARTS
+
+
 def select_variant(M: int, N: int, K: int, layout) -> int:
     return lib().axonn_linear_select_variant(M, N, K, _layout(layout))
 
 
 def plan(M: int, N: int, K: int, layout) -> list:
-    """The launches behind one product: a list of dicts(variant, m, n, row0, col0), one or two."""
-    parts = (PlanPart * 2)()
+    """The launches behind one product: a list of dicts(variant, m, n, row0, col0), one to four."""
+    parts = (PlanPart * MAX_PLAN_PARTS)()
     n = lib().axonn_linear_plan(M, N, K, _layout(layout), parts)
     if n < 0:
         raise AxonnError(n, "axonn_linear_plan")

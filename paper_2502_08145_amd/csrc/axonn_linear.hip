@@ -14,6 +14,7 @@
 #include "gemm_mfma.hpp"
 #include "gemm_mfma16.hpp"
 #include "gemm_mfma16_k64.hpp"
+#include "gemm_edge.hpp"
 #include "comm_model.hpp"
 #include "transpose.hpp"
 
@@ -102,6 +103,7 @@ struct Variant {
     int splits;                      // K ranges per tile (1: no split-K)
     int base;                        // index of the variant whose measured efficiency applies
     tile_kernel_t fn[3];             // per layout
+    bool edge = false;               // the guarded MFMA kernel: any shape, launched through launch_edge
 };
 
 #define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN, SPLITS, BASE)                                       \
@@ -185,8 +187,12 @@ static const Variant g_variants[] = {
     AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk6", 4, 6, 15),
     AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk7", 4, 7, 15),
     AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk8", 4, 8, 15),
+    // guarded MFMA kernel: ragged shapes and the edge strips of ragged outputs
+    {"mfma16_edge_128x128", EdgeCfg::BM, EdgeCfg::BN, EdgeCfg::NT, EdgeCfg::LDS_BYTES, 1, 1, 1, 0, {nullptr, nullptr, nullptr}, true},
 };
 constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
+constexpr int kEdgeVariant = kNumVariants - 1;
+static bool is_guarded(int v) { return g_variants[v].bm == 0 || g_variants[v].edge; }
 
 // Split-K scratch: one area per device.  Layout: kFlagBytes of flags (one 32-bit flag per slot, the
 // time-out counter in the last word), then `slots` slots of one 256x256 fp32 tile.  Either the
@@ -251,8 +257,9 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
     if (v < 0 || v >= kNumVariants || layout < 0 || layout > 2) return false;
     const Variant& var = g_variants[v];
     if (var.bm == 0) return true;
-    if (!var.fn[layout]) return false;   // a kernel for one layout only
     if (M <= 0 || N <= 0 || K <= 0) return false;
+    if (var.edge) return ((M + var.bm - 1) / var.bm) * ((N + var.bn - 1) / var.bn) < ((int64_t)1 << 31);
+    if (!var.fn[layout]) return false;   // a kernel for one layout only
     // per-lane address offsets are 32 bits: up to 16 rows of a K-contiguous operand, 4 (64-k kernel: 36)
     // k-rows of an MN-contiguous one, plus the K window of a K-contiguous one
     constexpr int64_t kMaxTileDim = (int64_t)1 << 24;
@@ -315,8 +322,19 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     return rounds * var.bm * var.bn * k_cost / eff[layout][var.base];
 }
 
-// The variant with the smallest modelled time for one launch over the whole output (0, the naive
-// kernel, if no tile shape divides it); *t_out receives that time.
+// What the guarded MFMA kernel takes for an m x n block, in the model's units (2.6e6 to the
+// microsecond: a 256 x 256 tile over K = 4096 is 2.7e8 and takes about 100 us).  Its K-steps of
+// 128 are a chain of load, barrier, LDS store, barrier, multiply: measured 1.9 us per step for a
+// workgroup that has a compute unit to itself, 1.6 us with the chip full (two to a CU, 205 us for
+// 4096^3 in 1024 workgroups), plus launch and epilogue.
+static double edge_time(int64_t m, int64_t n, int64_t K) {
+    const double wgs = (double)(((m + EdgeCfg::BM - 1) / EdgeCfg::BM) * ((n + EdgeCfg::BN - 1) / EdgeCfg::BN));
+    const double steps = (double)((K + EdgeCfg::BK - 1) / EdgeCfg::BK);
+    return (3.0 + steps * 2.0 * std::max(1.0, wgs / 320.0)) * 2.6e6;
+}
+
+// The variant with the smallest modelled time for one launch over the whole output (the guarded MFMA
+// kernel if no tile shape divides it; 0, the naive kernel, for K = 0); *t_out receives that time.
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split, double* t_out = nullptr) {
     int best = 0;
     double best_t = 0;
@@ -326,6 +344,10 @@ static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allo
             best = v;
             best_t = t;
         }
+    }
+    if (best == 0 && variant_supports(kEdgeVariant, M, N, K, layout)) {
+        best = kEdgeVariant;
+        best_t = edge_time(M, N, K);
     }
     if (t_out) *t_out = best_t;
     return best;
@@ -343,14 +365,34 @@ struct Part {
 };
 struct Plan {
     int parts;
-    Part part[2];
+    Part part[AXONN_MAX_PLAN_PARTS];
 };
+static_assert(AXONN_MAX_PLAN_PARTS >= 4, "two launches over whole tiles and two edge strips");
 
 static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
     double t_one = 0;
-    Plan plan{1, {{select_variant(M, N, K, layout, allow_split, &t_one), M, N, 0, 0}, {0, 0, 0, 0, 0}}};
+    Plan plan{1, {{select_variant(M, N, K, layout, allow_split, &t_one), M, N, 0, 0}}};
+    if (is_guarded(plan.part[0].variant)) {
+        // Ragged output of some size: the whole 128 x 128 tiles go to the tile kernels (if K suits
+        // them), the last columns and the last rows to the guarded kernel, as strips of their own.
+        const int64_t mm = M - M % 128, nm = N - N % 128;
+        if (mm > 0 && nm > 0 && (mm != M || nm != N)) {
+            constexpr double kNextLaunch = 8.0e6;   // about 3 us, as for the two-launch plans below
+            double t_tiles = 0;
+            const int v_tiles = select_variant(mm, nm, K, layout, allow_split, &t_tiles);
+            const double t_strips = (nm != N ? edge_time(mm, N - nm, K) + kNextLaunch : 0.0) +
+                                    (mm != M ? edge_time(M - mm, N, K) + kNextLaunch : 0.0);
+            if (!is_guarded(v_tiles) && t_tiles + t_strips < t_one) {
+                const Plan inner = make_plan(mm, nm, K, layout, allow_split);
+                plan = inner;
+                if (nm != N) plan.part[plan.parts++] = Part{kEdgeVariant, mm, N - nm, 0, nm};
+                if (mm != M) plan.part[plan.parts++] = Part{kEdgeVariant, M - mm, N, mm, 0};
+            }
+        }
+        return plan;
+    }
     // nothing to gain within half a round of large tiles: split-K and the smaller tiles cover that
-    if (plan.part[0].variant == 0 || M % 128 != 0 || N % 128 != 0 || (M / 128) * (N / 128) <= 4 * 128) return plan;
+    if (M % 128 != 0 || N % 128 != 0 || (M / 128) * (N / 128) <= 4 * 128) return plan;
     // what a second launch costs beyond its own fill and drain (the first one's tail is not
     // overlapped), in the model's units: about 3 us
     constexpr double kSecondLaunch = 8.0e6;
@@ -362,7 +404,7 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_sp
         double t1 = 0, t2 = 0;
         const int v1 = select_variant(m1, n1, K, layout, allow_split, &t1);
         const int v2 = select_variant(m2, n2, K, layout, allow_split, &t2);
-        if (v1 == 0 || v2 == 0 || t1 + t2 + kSecondLaunch >= best_t) return;
+        if (is_guarded(v1) || is_guarded(v2) || t1 + t2 + kSecondLaunch >= best_t) return;
         best_t = t1 + t2 + kSecondLaunch;
         plan = Plan{2, {{v1, m1, n1, 0, 0}, {v2, m2, n2, along_n ? 0 : m1, along_n ? n1 : 0}}};
     };
@@ -414,12 +456,15 @@ static void raise_lds_limits() {
             if (g_variants[v].fn[l])
                 (void)hipFuncSetAttribute(reinterpret_cast<const void*>(g_variants[v].fn[l]),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, g_variants[v].lds_bytes);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<true, false>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
     (void)hipGetLastError();
 }
 
 static size_t split_bytes(const Part& p) {
     const Variant& x = g_variants[p.variant];
-    return x.bm == 0 ? 0 : (size_t)((p.m / x.bm) * (p.n / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
+    return x.splits == 1 ? 0 : (size_t)((p.m / x.bm) * (p.n / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
 }
 
 static size_t split_bytes(const Plan& plan) {
@@ -428,7 +473,13 @@ static size_t split_bytes(const Plan& plan) {
     return bytes;   // the launches of a plan run one after the other and share the area
 }
 
-// One tile-kernel launch over the block `p` of the M x N output.
+// workgroups of the launch over block `p`
+static int64_t part_workgroups(const Part& p) {
+    const Variant& var = g_variants[p.variant];
+    return ((p.m + var.bm - 1) / var.bm) * ((p.n + var.bn - 1) / var.bn) * var.splits;
+}
+
+// One kernel launch over the block `p` of the M x N output.
 static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layout, const uint16_t* A, const uint16_t* B,
                         uint16_t* C, const Scratch& scratch, hipStream_t s) {
     const Variant& var = g_variants[p.variant];
@@ -436,6 +487,16 @@ static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layo
     A += layout == AXONN_TN ? p.row0 : p.row0 * K;
     B += layout == AXONN_NT ? p.col0 * K : p.col0;
     C += p.row0 * N + p.col0;
+    if (var.edge) {
+        const int tiles_n = (int)((p.n + var.bn - 1) / var.bn);
+        const dim3 grid((unsigned)part_workgroups(p)), block(var.threads);
+        switch (layout) {
+            case AXONN_NN: hipLaunchKernelGGL((gemm_edge_kernel<true, false>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
+            case AXONN_NT: hipLaunchKernelGGL((gemm_edge_kernel<true, true>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
+            default:       hipLaunchKernelGGL((gemm_edge_kernel<false, false>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
+        }
+        return;
+    }
     const int tiles_m = (int)(p.m / var.bm), tiles_n = (int)(p.n / var.bn);
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
     const int group_m = tiles_m < 8 ? tiles_m : 8;
@@ -460,7 +521,7 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     Scratch scratch;
     if (forced >= 0) {
         if (!variant_supports(forced, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
-        plan = Plan{1, {{forced, M, N, 0, 0}, {0, 0, 0, 0, 0}}};
+        plan = Plan{1, {{forced, M, N, 0, 0}}};
         if (split_bytes(plan) && !(scratch = get_scratch(split_bytes(plan))).partials) return AXONN_ERR_WORKSPACE;
     } else {
         plan = cached_plan(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
@@ -483,10 +544,8 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
         }
     } else {
         std::call_once(g_attr_once, raise_lds_limits);
-        for (int i = 0; i < plan.parts; ++i) {
-            const Variant& var = g_variants[plan.part[i].variant];
-            if ((plan.part[i].m / var.bm) * (plan.part[i].n / var.bn) >= ((int64_t)1 << 31) / var.splits) return AXONN_ERR_UNSUPPORTED;
-        }
+        for (int i = 0; i < plan.parts; ++i)
+            if (part_workgroups(plan.part[i]) >= ((int64_t)1 << 31)) return AXONN_ERR_UNSUPPORTED;
         for (int i = 0; i < plan.parts; ++i) launch_part(plan.part[i], M, N, K, layout, A, B, C, scratch, s);
     }
     return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
@@ -642,7 +701,7 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout) {
     return axonn::select_variant(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
 }
 
-int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[2]) {
+int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[AXONN_MAX_PLAN_PARTS]) {
     if (M <= 0 || N <= 0 || K < 0 || layout < 0 || layout > 2 || !parts) return AXONN_ERR_INVALID_ARG;
     const axonn::Plan plan = axonn::cached_plan(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
     for (int i = 0; i < plan.parts; ++i)

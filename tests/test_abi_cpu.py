@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2502_08145_amd import binding as B
@@ -74,10 +75,14 @@ def test_variant_table_and_selection():
     assert B.variant_name(n) is None and B.variant_name(-1) is None
     names = [B.variant_name(v) for v in range(n)]
     assert len(set(names)) == n
-    # the guarded kernel takes everything, tile kernels only whole tiles
+    # the guarded kernels take everything (the MFMA one wants K >= 1), tile kernels only whole tiles
+    edge = names.index("mfma16_edge_128x128")
+    assert edge == n - 1
     for lay in ("NN", "NT", "TN"):
-        assert B.variant_supports(0, 3, 5, 7, lay)
-        for v in range(1, n):
+        assert B.variant_supports(0, 3, 5, 7, lay) and B.variant_supports(0, 256, 256, 0, lay)
+        assert B.variant_supports(edge, 3, 5, 7, lay) and B.variant_supports(edge, 1024, 1024, 1024, lay)
+        assert not B.variant_supports(edge, 256, 256, 0, lay)
+        for v in range(1, edge):
             assert not B.variant_supports(v, 100, 200, 300, lay)
             assert B.variant_supports(v, 1024, 1024, 64 * 840, lay)          # 840 = lcm(1..8) K ranges
             assert not B.variant_supports(v, 1024, 1024, 1000, lay)
@@ -95,7 +100,8 @@ def test_variant_table_and_selection():
             slots = (4096 // bm) * (4096 // bn) * (splits - 1)
             assert B.variant_supports(v, 4096, 4096, 4096, lay) == (slots <= 1023 and slots * bm * bn * 4 <= 64 << 20)
         # ragged or degenerate shapes go to the guarded kernel, large ones to an MFMA kernel
-        assert B.select_variant(100, 200, 300, lay) == 0
+        assert B.select_variant(100, 200, 300, lay) == edge
+        assert B.select_variant(1024, 1024, 1000, lay) == edge
         assert B.select_variant(256, 256, 0, lay) == 0
         for shape in [(2048, 12288, 4096), (4096, 16384, 2048), (8192, 8192, 8192), (2048, 8192, 2048)]:
             v = B.select_variant(*shape, lay)
@@ -167,6 +173,8 @@ def test_plan_blocks_tile_the_output_and_their_variants_fit(shape, layout):
     M, N, K = shape
     parts = B.plan(M, N, K, layout)
     assert 1 <= len(parts) <= 2
+    for p in parts:
+        assert B.variant_name(p["variant"]) != "mfma16_edge_128x128" or (M % 128 or N % 128)
     first = parts[0]
     assert (first["row0"], first["col0"]) == (0, 0)
     if len(parts) == 1:
@@ -185,6 +193,50 @@ def test_plan_blocks_tile_the_output_and_their_variants_fit(shape, layout):
     for p in parts:
         assert p["variant"] > 0 or len(parts) == 1
         assert B.variant_supports(p["variant"], p["m"], p["n"], K, layout)
+
+
+@pytest.mark.parametrize("shape", [(2048 + 40, 4096 + 72, 1024), (2048, 4096 + 8, 4096), (2048 + 1, 4096, 4096),
+                                   (2048 + 100, 12288 + 1, 4096), (129, 129, 65536), (1000, 1000, 1024),
+                                   (4096, 4100, 1000), (200, 200, 64), (127, 4096, 4096), (4096, 5, 4096),
+                                   (4096 + 8, 8192 + 8, 2048)])
+@pytest.mark.parametrize("layout", ["NN", "NT", "TN"])
+def test_plan_of_a_ragged_output_whole_tiles_then_edge_strips(shape, layout):
+    M, N, K = shape
+    parts = B.plan(M, N, K, layout)
+    assert 1 <= len(parts) <= B.MAX_PLAN_PARTS
+    edge = B.num_variants() - 1
+    # the blocks are disjoint and cover the output
+    cover = np.zeros((M, N), np.uint8)
+    for p in parts:
+        assert p["m"] > 0 and p["n"] > 0 and p["row0"] >= 0 and p["col0"] >= 0
+        assert p["row0"] + p["m"] <= M and p["col0"] + p["n"] <= N
+        cover[p["row0"]:p["row0"] + p["m"], p["col0"]:p["col0"] + p["n"]] += 1
+        assert B.variant_supports(p["variant"], p["m"], p["n"], K, layout)
+    assert cover.min() == 1 and cover.max() == 1
+    mm, nm = M - M % 128, N - N % 128
+    tiled = [p for p in parts if p["variant"] != edge]
+    strips = [p for p in parts if p["variant"] == edge]
+    if tiled:
+        # tile kernels on the whole tiles, the guarded kernel on what is left
+        assert K % 64 == 0 and sum(p["m"] * p["n"] for p in tiled) == mm * nm
+        assert len(strips) == (M != mm) + (N != nm)
+        assert B.axonn_linear_workspace_bytes(M, N, K, layout) == B.axonn_linear_workspace_bytes(mm, nm, K, layout)
+    else:
+        assert len(parts) == 1
+
+
+def test_ragged_plan_takes_strips_only_where_they_pay():
+    # a strip is a chain of K/128 steps of about 2 us each: worth it beside a large tiled part ...
+    edge = B.num_variants() - 1
+    for shape in [(2049, 16384, 4096), (2048, 16392, 4096), (4096 + 8, 8192 + 8, 2048), (2048 + 100, 12288 + 1, 4096)]:
+        for lay in ("NN", "NT", "TN"):
+            parts = B.plan(*shape, lay)
+            assert len(parts) >= 2 and parts[0]["variant"] != edge and parts[-1]["variant"] == edge, (shape, lay, parts)
+    # ... and not beside a small one, nor when K does not suit the tile kernels
+    for shape in [(2088, 4168, 1024), (1064, 1608, 768), (200, 200, 64), (4096, 4100, 1000), (2049, 16384, 4010)]:
+        for lay in ("NN", "NT", "TN"):
+            parts = B.plan(*shape, lay)
+            assert len(parts) == 1 and parts[0]["variant"] == edge, (shape, lay, parts)
 
 
 def test_plan_cuts_one_and_a_half_rounds_and_leaves_whole_rounds_alone():

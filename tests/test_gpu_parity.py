@@ -42,9 +42,31 @@ def run_gpu(op, M, N, K, layout, A_bits, B_bits, variant=-1, stream=None, poison
     return U.to_host_bits(c)
 
 
+def run_gpu_guard_rows(op, M, N, K, layout, A_bits, B_bits, variant=-1):
+    """run_gpu with two more rows behind the output, which must come back untouched."""
+    a, b = U.to_device(A_bits), U.to_device(B_bits)
+    buf = torch.empty((M + 2, N), dtype=torch.bfloat16, device="cuda")
+    buf.view(torch.int16).fill_(0x7FC0)
+    B.force_variant(variant)
+    try:
+        B.OPS[op](M, N, K, layout, a, b, buf[:M], 1, None)
+    finally:
+        B.force_variant(-1)
+    torch.cuda.synchronize()
+    host = U.to_host_bits(buf)
+    assert (host[M:] == 0x7FC0).all(), "rows behind the output were written"
+    return host[:M]
+
+
 def tile_variants(layout=None):
-    """All MFMA tile variants (every one has a kernel for every layout)."""
-    return [v for v in range(1, B.num_variants())]
+    """All MFMA tile variants (every one has a kernel for every layout); the last variant is the guarded one."""
+    return [v for v in range(1, edge_variant())]
+
+
+def edge_variant():
+    v = B.num_variants() - 1
+    assert B.variant_name(v) == "mfma16_edge_128x128"
+    return v
 
 
 def splits_of(v):
@@ -80,10 +102,82 @@ def test_ragged_shapes_any_size(oracle_mod, layout, shape):
     b = synth.normal_bf16(2000 + N, (K, N), 0.02)
     A, Bm = store(a, b, layout)
     ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
-    assert B.select_variant(M, N, K, layout) == 0
+    assert B.select_variant(M, N, K, layout) == edge_variant()
     for op in OPS:
         got = run_gpu(op, M, N, K, layout, A, Bm)
         U.assert_close(got, ref, f"{op} {layout} {shape}")
+    got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=0)
+    U.assert_close(got, ref, f"naive {layout} {shape}")
+
+
+# ------------------------------------------------------------------ the guarded MFMA kernel
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", [(300, 270, 100), (257, 129, 200), (128, 128, 32), (129, 127, 31), (640, 384, 352),
+                                   (5, 1000, 515), (1000, 5, 1027), (264, 392, 8)])
+def test_guarded_mfma_kernel_bit_exact_on_integers(oracle_mod, layout, shape):
+    # several tiles, ragged tails in all three directions, leading dimensions that leave rows at odd
+    # addresses (no vector loads), K shorter than a K-step; small integers: the sum is exact in
+    # fp32 and the output must equal the rounded oracle bit for bit
+    M, N, K = shape
+    a = synth.integer_bf16(500 + M, (M, K), -4, 4)
+    b = synth.integer_bf16(600 + N, (K, N), -4, 4)
+    A, Bm = store(a, b, layout)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
+    got = run_gpu_guard_rows("fwd", M, N, K, layout, A, Bm, variant=edge_variant())
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{layout} {shape}: {len(bad)} mismatches, first at {bad[0]}"
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_guarded_mfma_kernel_against_oracle_normal_data(oracle_mod, layout):
+    for M, N, K in [(768, 768, 416), (391, 1003, 777)]:
+        a = synth.normal_bf16(71 + M, (M, K))
+        b = synth.normal_bf16(72 + N, (K, N), 0.02)
+        A, Bm = store(a, b, layout)
+        ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+        got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=edge_variant())
+        nw, ew = U.assert_close(got, ref, f"edge {layout} {(M, N, K)}")
+        assert nw < 4e-3, nw
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("shape", [(1024 + 40, 1536 + 72, 768), (1152, 1024 + 8, 1024), (1024 + 1, 1280, 1024)])
+def test_ragged_output_of_several_tiles_every_element(oracle_mod, layout, shape):
+    # every element, bit for bit on integer data, through all three entry points, and nothing
+    # written behind the output
+    M, N, K = shape
+    a = synth.integer_bf16(700 + M, (M, K), -4, 4)
+    b = synth.integer_bf16(800 + N, (K, N), -4, 4)
+    A, Bm = store(a, b, layout)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
+    for op in OPS:
+        got = run_gpu_guard_rows(op, M, N, K, layout, A, Bm)
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, f"{op} {layout} {shape}: {len(bad)} mismatches, first at {bad[0]}"
+
+
+@pytest.mark.parametrize("shape", [(4096 + 8, 8192 + 8, 2048), (2048 + 1, 8192, 2048), (4096, 8192 + 100, 2048)])
+def test_ragged_output_as_tiles_plus_edge_strips_sampled(oracle_mod, shape):
+    """A large ragged output: whole tiles by the tile kernels, the last columns and the last rows by
+    the guarded kernel as launches of their own.  Integer data; the strips in full, the tiled part
+    on sampled rows, columns and one element per 128 x 128 block, bit for bit."""
+    M, N, K = shape
+    mm, nm = M - M % 128, N - N % 128
+    a = synth.integer_bf16(900 + M, (M, K), -4, 4)
+    b = synth.integer_bf16(901 + N, (K, N), -4, 4)
+    ii, jj = _sample_positions(M, N, seed=M + N)
+    si, sj = np.nonzero(np.add.outer(np.arange(M) >= mm, np.arange(N) >= nm))   # the strips, every element
+    ii, jj = np.concatenate([ii, si]), np.concatenate([jj, sj])
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, "NN", a, b, ii, jj))
+    for layout in LAYOUTS:
+        parts = B.plan(M, N, K, layout)
+        assert len(parts) >= 1 + (M != mm) + (N != nm) and parts[0]["variant"] != edge_variant(), parts
+        assert [p["variant"] for p in parts].count(edge_variant()) == (M != mm) + (N != nm)
+        A, Bm = store(a, b, layout)
+        got = run_gpu_guard_rows("fwd", M, N, K, layout, A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all(), f"{shape} {layout}: unwritten or non-finite output"
+        bad = np.nonzero(got[ii, jj] != want)[0]
+        assert bad.size == 0, f"{layout} {shape}: {len(bad)} mismatches, first at {(ii[bad[0]], jj[bad[0]])}"
 
 
 def test_k_zero_gives_zero_and_empty_outputs_are_ok():
