@@ -116,6 +116,7 @@ def main():
                          "GEMM mode (HBM-bound side kernel; reports GB/s instead of TFLOP/s)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-power-sample", action="store_true", help="skip the amd-smi reading of power and clock")
     ap.add_argument("--tune", action="store_true",
                     help="after the timed region, run the mode tuner on every GEMM of the workload and log its table")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -252,6 +253,32 @@ def main():
     probe_tflops = cus * 4 * iters * 64 * 32768.0 / (p0.elapsed_time(p1) * 1e-3) / 1e12
     log(f"MFMA-only probe on the same N(0,1) values: {probe_tflops:.1f} TFLOP/s ({cus} CUs, registers only)")
 
+    # ---- context: board power and shader clock while the step runs (the published peak assumes 2.4 GHz) ----
+    board = None
+    if not args.no_power_sample:
+        try:
+            from paper_2502_08145_amd.sweeps import smi_sample
+            watts, mhz = [], []
+            for _ in range(2):
+                for _ in range(max(1, int(1200.0 / ms_per_step))):     # about 1.2 s of queued steps, sampled while they run
+                    for g in gemms:
+                        launch(g)
+                w, clk = smi_sample()
+                torch.cuda.synchronize()
+                if w is not None and clk:
+                    watts.append(w)
+                    mhz += clk
+            if mhz:
+                sclk = sum(mhz) / len(mhz)
+                board = {"socket_w": round(sum(watts) / len(watts)), "sclk_mhz": round(sclk),
+                         "peak_at_sclk": round(PEAK_BF16_TFLOPS * sclk / 2400.0, 1),
+                         "frac_at_sclk": round(value / (PEAK_BF16_TFLOPS * sclk / 2400.0), 4)}
+                log(f"board under the step: {board['socket_w']} W, shader clock {board['sclk_mhz']} MHz "
+                    f"(peak at that clock {board['peak_at_sclk']} TFLOP/s, step at {board['frac_at_sclk'] * 100:.1f} % of it)")
+        except Exception as e:   # no amd-smi, or output in another format: context only
+            log(f"board power/clock not sampled: {e}")
+            torch.cuda.synchronize()
+
     if args.tune:
         # the paper's own optimisation (Sec. IV-C): each product timed in NN, NT and TN, with what it
         # costs to re-store the operands for the other modes
@@ -302,7 +329,7 @@ def main():
            "config": {"workload": args.workload, "gemms": len(gemms), "layouts": "natural (fwd NN, bwd_data NT, bwd_weight TN)",
                       "step_tflop": round(step_flops / 1e12, 4)},
            "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
-           "mfma_only_probe_tflops": round(probe_tflops, 1),
+           "mfma_only_probe_tflops": round(probe_tflops, 1), "board": board,
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 
