@@ -147,13 +147,7 @@ __device__ __forceinline__ void store_tile16(f32x4 (&acc)[MI][NI], uint8_t* smem
         __builtin_amdgcn_sched_barrier(0);   // convert block row by block row: keeps register pressure low
     }
     __syncthreads();
-#pragma unroll
-    for (int it = 0; it < (TM * CPR) / 64; ++it) {
-        const uint32_t idx = it * 64 + lane;
-        const uint32_t row = idx / CPR, ch = idx % CPR;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + row * (TN * 2) + ((ch ^ (row & CMASK)) << 4));
-        *reinterpret_cast<u32x4*>(pc + (int64_t)row * ldc + ch * 8) = v;
-    }
+    flush_c_block<TM, TN>(epi, pc, ldc, lane);
 }
 
 // Requires M % BM == 0, N % BN == 0, K % 64 == 0, K >= TileCfg16::MIN_K (per K range when split).
