@@ -115,6 +115,10 @@ def main():
                     help="transpose_weights: re-store the four weight matrices of the gpt5b layer for another "
                          "GEMM mode (HBM-bound side kernel; reports GB/s instead of TFLOP/s)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--rotate", type=int, default=0, metavar="R",
+                    help="distinct copies of every operand and output, used in turn step by step, so that a small "
+                         "workload does not run out of the 256 MB Infinity Cache; 0 (default): as many as make the "
+                         "steps touch 768 MiB between them (1 for the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-power-sample", action="store_true", help="skip the amd-smi reading of power and clock")
     ap.add_argument("--tune", action="store_true",
@@ -147,22 +151,26 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
 
     # ---- synthetic operands, resident in HBM before any timing ---------------------------
-    gemms = []        # dict(name, op, layout, M, N, K, a, b, c, flops, host=(A_bits, B_bits))
+    gemms = []        # dict(name, op, layout, M, N, K, a, b, c, flops, host=(A_bits, B_bits)); a, b, c: one per operand set
     seed = synth.BASE_SEED + 100 * sorted(LAYERS).index(args.workload)
+    step_bytes = sum(2 * (tk * di + di * do + tk * do) + 2 * (tk * do + tk * di + di * do)
+                     for _, tk, di, do in LAYERS[args.workload])          # X, W, dY and the three outputs of a layer
+    sets = args.rotate if args.rotate > 0 else (1 if step_bytes >= (512 << 20) else min(256, -(-(768 << 20) // step_bytes)))
     for li, (tag, tokens, d_in, d_out) in enumerate(LAYERS[args.workload]):
         t = synth.fc_layer_tensors(tokens, d_in, d_out, seed + 10 * li)
-        dev_t = {k: up(v) for k, v in t.items()}
+        dev_t = [{k: up(v) for k, v in t.items()} for _ in range(sets)]
         for g in synth.fc_layer_gemms(tokens, d_in, d_out, tag):
             first, second = {"fwd": ("X", "W"), "bwd_data": ("dY", "W"), "bwd_weight": ("X", "dY")}[g["op"]]
             g = dict(g)
-            g["a"], g["b"] = dev_t[first], dev_t[second]
-            g["c"] = torch.empty((g["M"], g["N"]), dtype=torch.bfloat16, device=dev)
+            g["a"], g["b"] = [d[first] for d in dev_t], [d[second] for d in dev_t]
+            g["c"] = [torch.empty((g["M"], g["N"]), dtype=torch.bfloat16, device=dev) for _ in range(sets)]
             g["flops"] = 2.0 * g["M"] * g["N"] * g["K"]
             g["host"] = (t[first], t[second])
             g["variant"] = B.plan_name(g["M"], g["N"], g["K"], g["layout"])   # "a+b": two launches
             gemms.append(g)
     step_flops = sum(g["flops"] for g in gemms)
-    log(f"workload {args.workload}: {len(gemms)} GEMMs, {step_flops / 1e12:.3f} TFLOP per step")
+    log(f"workload {args.workload}: {len(gemms)} GEMMs, {step_flops / 1e12:.3f} TFLOP per step, {step_bytes / 1e6:.0f} MB of "
+        f"operands and outputs per step, {sets} operand set(s) used in turn")
 
     if args.calibrate_copy > 0:
         n = args.calibrate_copy * (1 << 20) // 2
@@ -177,12 +185,12 @@ def main():
 
     stream = torch.cuda.current_stream()
 
-    def launch(g):
-        B.OPS[g["op"]](g["M"], g["N"], g["K"], g["layout"], g["a"], g["b"], g["c"], 1, stream)
+    def launch(g, r=0):
+        B.OPS[g["op"]](g["M"], g["N"], g["K"], g["layout"], g["a"][r], g["b"][r], g["c"][r], 1, stream)
 
-    for _ in range(args.warmup):
+    for w in range(args.warmup):
         for g in gemms:
-            launch(g)
+            launch(g, w % sets)
     torch.cuda.synchronize()
 
     # ---- timed region: K steps; every launch bracketed by HIP events on the launch stream --
@@ -194,7 +202,7 @@ def main():
         for gi, g in enumerate(gemms):
             e0, e1 = ev[s][gi]
             e0.record(stream)
-            launch(g)
+            launch(g, s % sets)
             e1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -210,7 +218,7 @@ def main():
             f"{ms * 1e3:8.1f} us  {g['flops'] / ms / 1e9:7.1f} TFLOP/s  {g['flops'] / ms / 1e9 / PEAK_BF16_TFLOPS * 100:5.1f}%"
             f"  {alg_bytes / ms / 1e6:6.0f} GB/s alg.")
     for g in gemms:
-        if not torch.isfinite(g["c"].float()).all():
+        if not all(torch.isfinite(c.float()).all() for c in g["c"]):
             sys.exit(f"bench.py: non-finite output in {g['name']}")
 
     # dominant kernel = the (variant, layout) instance with the largest summed time, among the
@@ -240,7 +248,7 @@ def main():
 
     # ---- context: what the matrix pipes sustain on these operand values with no data movement ----
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    pdata = gemms[0]["a"].reshape(-1)[: 1 << 20]          # N(0,1) activations of the first layer
+    pdata = gemms[0]["a"][0].reshape(-1)[: 1 << 20]          # N(0,1) activations of the first layer
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     iters = 4000
     B.axonn_linear_mfma_probe(pdata, 200, cus, sink, stream)
@@ -286,7 +294,7 @@ def main():
         names = ["NN", "NT", "TN"]
         for g in gemms:
             scratch = torch.empty(((g["M"] * g["K"] * 2 + 255) // 256 * 256 + g["K"] * g["N"] * 2,), dtype=torch.uint8, device=dev)
-            r = B.axonn_linear_tune(g["op"], g["M"], g["N"], g["K"], g["a"], g["b"], g["c"], scratch, stream)
+            r = B.axonn_linear_tune(g["op"], g["M"], g["N"], g["K"], g["a"][0], g["b"][0], g["c"][0], scratch, stream)
             cells = "  ".join(f"{names[m]} {r['gemm_us'][m]:7.1f} (+{r['restore_first_us'][m] + r['restore_second_us'][m]:6.1f})"
                               for m in range(3))
             log(f"  {g['name']:<22s} natural {g['layout']}: {cells}  best {names[r['best_layout']]}, "
@@ -327,7 +335,7 @@ def main():
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": args.workload, "gemms": len(gemms), "layouts": "natural (fwd NN, bwd_data NT, bwd_weight TN)",
-                      "step_tflop": round(step_flops / 1e12, 4)},
+                      "step_tflop": round(step_flops / 1e12, 4), "operand_sets": sets},
            "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
            "mfma_only_probe_tflops": round(probe_tflops, 1), "board": board,
            "roofline": roofline, "cpu_baseline": cpu}
