@@ -178,6 +178,35 @@ def power_clock(args):
             print(f"{M:6d} {N:6d} {K:6d} {layout:>4s} {name:<28s} {tf:8.1f} {sum(watts) / len(watts):5.0f} {mean:8.0f} "
                   f"{min(mhz):5d} {max(mhz):5d} {tf / at_clock * 100:23.1f}%", flush=True)
         del a, b, c
+    # the matrix pipes alone, on N(0,1) operand values held in registers: what the board's power limit
+    # leaves of the clock when nothing but MFMAs run
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    data = randn_bf16((1 << 20,), 1.0, gen)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    iters = 4000
+    for _ in range(200):     # about a second: clocks and power settle
+        B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(20):
+        B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 20
+    watts, mhz = [], []
+    for _ in range(3):
+        for _ in range(int(1500.0 / ms)):
+            B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
+        w, clk = smi_sample()
+        torch.cuda.synchronize()
+        if w is not None and clk:
+            watts.append(w)
+            mhz += clk
+    tf = cus * 4 * iters * 64 * 32768.0 / (ms * 1e-3) / 1e12
+    mean = sum(mhz) / len(mhz)
+    print(f"{'':>6s} {'':>6s} {'':>6s} {'':>4s} {'MFMA-only probe, N(0,1)':<28s} {tf:8.1f} {sum(watts) / len(watts):5.0f} {mean:8.0f} "
+          f"{min(mhz):5d} {max(mhz):5d} {tf / (PEAK * mean / 2400.0) * 100:23.1f}%", flush=True)
 
 
 def main(argv=None):
