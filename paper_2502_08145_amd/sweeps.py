@@ -110,12 +110,16 @@ def model_zoo(args):
               f"{flops_sum / ms_sum / 1e9:9.1f}  {worst[1]} ({worst[0]:.0f} TFLOP/s)", flush=True)
 
 
-def smi_sample():
-    """(socket power in W, [shader clock of each XCD in MHz]) as amd-smi prints them right now."""
-    out = subprocess.run(["amd-smi", "metric", "-c", "-p"], capture_output=True, text=True, timeout=30).stdout
-    power = re.search(r"SOCKET_POWER:\s*(\d+)\s*W", out)
-    clocks = [int(m) for m in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)\s*MHz", out)]
+def parse_smi(text):
+    """(socket power in W or None, [shader clock of each XCD in MHz]) from the text of `amd-smi metric -c -p`."""
+    power = re.search(r"SOCKET_POWER:\s*(\d+)\s*W", text)
+    clocks = [int(m) for m in re.findall(r"GFX_\d+:\s*\n\s*CLK:\s*(\d+)\s*MHz", text)]
     return (int(power.group(1)) if power else None), clocks
+
+
+def smi_sample():
+    """Power and shader clocks as amd-smi prints them right now."""
+    return parse_smi(subprocess.run(["amd-smi", "metric", "-c", "-p"], capture_output=True, text=True, timeout=30).stdout)
 
 
 def power_clock(args):

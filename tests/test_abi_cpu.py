@@ -260,3 +260,24 @@ def test_plan_rejects_bad_arguments():
     assert L.axonn_linear_plan(0, 128, 128, 0, parts) == B.AXONN_ERR_INVALID_ARG
     assert L.axonn_linear_plan(128, 128, 128, 3, parts) == B.AXONN_ERR_INVALID_ARG
     assert L.axonn_linear_plan(128, 128, 128, 0, ctypes.cast(None, ctypes.POINTER(B.PlanPart))) == B.AXONN_ERR_INVALID_ARG
+
+
+def test_amd_smi_text_is_parsed():
+    from paper_2502_08145_amd.sweeps import parse_smi
+    text = """GPU: 0
+    POWER:
+        SOCKET_POWER: 1398 W
+        GFX_VOLTAGE: N/A
+    CLOCK:
+        GFX_0:
+            CLK: 1915 MHz
+            MIN_CLK: 500 MHz
+            MAX_CLK: 2400 MHz
+        GFX_1:
+            CLK: 1865 MHz
+            MIN_CLK: 500 MHz
+        MEM_0:
+            CLK: 2000 MHz
+"""
+    assert parse_smi(text) == (1398, [1915, 1865])
+    assert parse_smi("no such fields") == (None, [])

@@ -379,8 +379,12 @@ def test_tiny_mlp_all_ops_all_layouts(oracle_mod):
 
 
 # ------------------------------------------------------------------ determinism, streams, errors
-def test_same_inputs_same_bits_and_side_stream(oracle_mod):
-    M, N, K = 1024, 512, 1024
+@pytest.mark.parametrize("shape,kind", [((1024, 512, 1024), "mfma"), ((2048, 4096, 16384), "_sk"),
+                                        ((1000, 520, 1031), "mfma16_edge"), ((2049, 8192, 2048), "+mfma16_edge")])
+def test_same_inputs_same_bits_and_side_stream(oracle_mod, shape, kind):
+    # a plain tile kernel, split-K (fixed reduction order), the guarded kernel, tiles plus an edge strip
+    M, N, K = shape
+    assert kind in B.plan_name(M, N, K, "NN")
     a = synth.normal_bf16(61, (M, K))
     b = synth.normal_bf16(62, (K, N))
     first = run_gpu("fwd", M, N, K, "NN", a, b)
