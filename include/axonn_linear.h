@@ -208,7 +208,8 @@ int axonn_linear_set_workspace(void *dev_ptr, size_t bytes);
 
 /* Optional set-up for the current device: raises the kernels' LDS limits and allocates the split-K
  * scratch area now rather than inside the first call that needs it (do this before capturing calls
- * into a HIP graph: an allocation is not allowed during capture).  Idempotent.  AXONN_OK, or
+ * into a HIP graph: an allocation is not allowed during capture; captured calls, split-K ones
+ * included, may be replayed any number of times on one stream).  Idempotent.  AXONN_OK, or
  * AXONN_ERR_WORKSPACE if the allocation failed (the library then works without split-K). */
 int axonn_linear_init(void);
 

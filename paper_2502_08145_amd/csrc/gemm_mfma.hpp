@@ -422,9 +422,9 @@ struct OperandMNContig {   // global P[k * ld + row]
 // readers that depend on them and a reader's wait always ends; the wait is bounded anyway.
 struct SplitK {
     float* partials;      // [(splits-1) * tiles] slots of BM*BN floats, in accumulator order
-    uint32_t* flags;      // [(splits-1) * tiles]; a slot is valid when its flag equals `epoch`
+    uint32_t* flags;      // [(splits-1) * tiles]; a slot is valid when its flag equals `epoch`; the reader resets it to 0
     uint32_t* timeouts;   // incremented when a reader gives up waiting (never, unless a writer died)
-    uint32_t epoch;       // differs from launch to launch: flags need no clearing
+    uint32_t epoch;       // non-zero, differs from launch to launch: a flag left behind by a launch that died is never valid
     int splits;           // 1: no split
 };
 constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~3 us per probe
@@ -817,6 +817,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel(
                     for (int e = 0; e < 4; ++e) acc[i][q / 4][4 * (q % 4) + e] += v[q][e];
                 AXONN_FENCE();
             }
+            // the slot is consumed: take its flag down again (a launch replayed from a captured HIP
+            // graph carries the epoch of its capture)
+            __syncthreads();
+            if (t == 0) __hip_atomic_store(&sk.flags[slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 

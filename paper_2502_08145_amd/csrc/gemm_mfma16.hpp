@@ -120,6 +120,10 @@ __device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const S
             for (int j = 0; j < NI; ++j) acc[i][j] += v[j];
             __builtin_amdgcn_sched_barrier(0);
         }
+        // The slot is consumed: take its flag down again.  A launch replayed from a captured HIP graph
+        // carries the epoch of its capture, and must not find that value left over from the replay before.
+        __syncthreads();
+        if (t == 0) __hip_atomic_store(&sk.flags[slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return false;
 }

@@ -300,6 +300,15 @@ def test_caller_owned_workspace(oracle_mod):
         B.axonn_linear_set_workspace(big)
         for rep in range(2):
             assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=sk2), want)
+        # every flag a writer raised has been taken down again by its reader (a launch replayed from
+        # a captured graph carries the same epoch again and must not find it standing)
+        flags = big[:4096].view(torch.int32).cpu().numpy()
+        assert not flags[:1023].any() and flags[1023] == 0, "split-K flags left standing, or a time-out"
+        # ... also by the other kernel families
+        for name in ("mfma16_256x256_w8_sk2", "mfma16k64_256x256_w8_sk2", "mfma16_128x128_sk2"):
+            v16 = [B.variant_name(v) for v in range(B.num_variants())].index(name)
+            assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=v16), want), name
+            assert not big[:4096].view(torch.int32).cpu().numpy().any(), name
         small = torch.zeros((4096 + 3 * 256 * 256 * 4,), dtype=torch.uint8, device="cuda")
         B.axonn_linear_set_workspace(small)
         B.force_variant(sk2)
@@ -394,6 +403,45 @@ def test_same_inputs_same_bits_and_side_stream(oracle_mod, shape, kind):
     with torch.cuda.stream(s):
         other = run_gpu("fwd", M, N, K, "NN", a, b, stream=s)
     assert np.array_equal(other, first)
+
+
+@pytest.mark.parametrize("variant,shape", [("mfma16_256x256_w8_sk2", (768, 768, 1792)), ("mfma16_128x128_sk4", (512, 384, 2048)),
+                                           ("mfma16k64_256x256_w8_sk3", (512, 768, 1536)), (None, (768, 512, 448))])
+def test_calls_captured_in_a_hip_graph_replay_correctly(variant, shape):
+    """A captured split-K launch carries the epoch of its capture into every replay: the flags it
+    raises must be down again when the next replay starts.  Replays alternate with eager work and
+    synchronisations, the inputs change between them, and every replay must give the bits of an
+    eager call on the same inputs."""
+    M, N, K = shape
+    names = [B.variant_name(v) for v in range(B.num_variants())]
+    v = names.index(variant) if variant else -1
+    assert v < 0 or B.variant_supports(v, M, N, K, "NT")
+    B.axonn_linear_init()
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    a = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
+    b = torch.randn((N, K), generator=gen, device="cuda").to(torch.bfloat16)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    c_eager = torch.empty_like(c)
+    B.force_variant(v)
+    try:
+        B.axonn_linear_bwd_data(M, N, K, "NT", a, b, c_eager)      # also raises the LDS limits before the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            B.axonn_linear_bwd_data(M, N, K, "NT", a, b, c, 1, torch.cuda.current_stream())
+        for rep in range(5):
+            a.copy_(torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16))
+            b.copy_(torch.randn((N, K), generator=gen, device="cuda").to(torch.bfloat16))
+            c.view(torch.int16).fill_(0x7FC0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            B.axonn_linear_bwd_data(M, N, K, "NT", a, b, c_eager)
+            torch.cuda.synchronize()
+            assert torch.equal(c.view(torch.int16), c_eager.view(torch.int16)), f"replay {rep} differs from the eager call"
+    finally:
+        B.force_variant(-1)
+    assert B.axonn_linear_split_k_timeouts() == 0
 
 
 def test_forced_variant_that_cannot_run_is_refused():
