@@ -251,7 +251,7 @@ static Scratch get_scratch(size_t bytes_needed) {
 }
 
 static std::atomic<int> g_forced{-1};
-static std::once_flag g_attr_once;
+static std::once_flag g_attr_once[kMaxDevices];   // the LDS limits are a per-device property of a kernel
 
 static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout) {
     if (v < 0 || v >= kNumVariants || layout < 0 || layout > 2) return false;
@@ -462,6 +462,17 @@ static void raise_lds_limits() {
     (void)hipGetLastError();
 }
 
+// once per device, the first time a kernel that needs it is about to be launched there
+static void raise_lds_limits_once() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        raise_lds_limits();
+        return;
+    }
+    std::call_once(g_attr_once[dev], raise_lds_limits);
+}
+
 static size_t split_bytes(const Part& p) {
     const Variant& x = g_variants[p.variant];
     return x.splits == 1 ? 0 : (size_t)((p.m / x.bm) * (p.n / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
@@ -543,7 +554,7 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
             default:       hipLaunchKernelGGL(gemm_naive_kernel<AXONN_TN>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
         }
     } else {
-        std::call_once(g_attr_once, raise_lds_limits);
+        raise_lds_limits_once();
         for (int i = 0; i < plan.parts; ++i)
             if (part_workgroups(plan.part[i]) >= ((int64_t)1 << 31)) return AXONN_ERR_UNSUPPORTED;
         for (int i = 0; i < plan.parts; ++i) launch_part(plan.part[i], M, N, K, layout, A, B, C, scratch, s);
@@ -710,7 +721,7 @@ int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_pa
 }
 
 int axonn_linear_init(void) {
-    std::call_once(axonn::g_attr_once, axonn::raise_lds_limits);
+    axonn::raise_lds_limits_once();
     return axonn::get_scratch(axonn::kSlotBytes).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
 }
 
