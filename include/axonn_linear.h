@@ -240,8 +240,9 @@ int axonn_linear_select_variant(int64_t M, int64_t N, int64_t K, int layout);
  * that suits it, e.g. the large tile for the first and split-K for the second.  Block i covers
  * rows row0 .. row0+m-1 and columns col0 .. col0+n-1 of the M x N output; the blocks are
  * disjoint and cover it.  A ragged output (M or N not a multiple of 128) whose K suits the tile
- * kernels is planned over its whole tiles as above, and the last columns and the last rows follow
- * as up to two blocks of the guarded MFMA kernel.  Writes parts[0 .. return value - 1] (HOST
+ * kernels, and whose rows start on 16-byte boundaries in all three matrices (N, and for TN also M,
+ * a multiple of 8), is planned over its whole tiles as above where that pays, and the last columns
+ * and the last rows follow as up to two blocks of the guarded MFMA kernel.  Writes parts[0 .. return value - 1] (HOST
  * memory, caller-owned, room for AXONN_MAX_PLAN_PARTS) and returns the number of launches, 1 to
  * AXONN_MAX_PLAN_PARTS; negative error code on bad arguments.  Pure host logic. */
 #define AXONN_MAX_PLAN_PARTS 4

@@ -376,7 +376,10 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_sp
         // Ragged output of some size: the whole 128 x 128 tiles go to the tile kernels (if K suits
         // them), the last columns and the last rows to the guarded kernel, as strips of their own.
         const int64_t mm = M - M % 128, nm = N - N % 128;
-        if (mm > 0 && nm > 0 && (mm != M || nm != N)) {
+        // the tile kernels move 16 bytes at a time: every row of the operands and of the output, as
+        // stored in the whole matrices, has to start on a 16-byte boundary (K is a multiple of 32 here)
+        const bool rows_aligned = N % 8 == 0 && (layout != AXONN_TN || M % 8 == 0);
+        if (mm > 0 && nm > 0 && (mm != M || nm != N) && rows_aligned) {
             constexpr double kNextLaunch = 8.0e6;   // about 3 us, as for the two-launch plans below
             double t_tiles = 0;
             const int v_tiles = select_variant(mm, nm, K, layout, allow_split, &t_tiles);

@@ -156,7 +156,7 @@ def test_ragged_output_of_several_tiles_every_element(oracle_mod, layout, shape)
         assert bad.size == 0, f"{op} {layout} {shape}: {len(bad)} mismatches, first at {bad[0]}"
 
 
-@pytest.mark.parametrize("shape", [(4096 + 8, 8192 + 8, 2048), (2048 + 1, 8192, 2048), (4096, 8192 + 100, 2048)])
+@pytest.mark.parametrize("shape", [(4096 + 8, 8192 + 8, 2048), (2048 + 1, 8192, 2048), (4096, 8192 + 104, 2048)])
 def test_ragged_output_as_tiles_plus_edge_strips_sampled(oracle_mod, shape):
     """A large ragged output: whole tiles by the tile kernels, the last columns and the last rows by
     the guarded kernel as launches of their own.  Integer data; the strips in full, the tiled part
@@ -171,8 +171,11 @@ def test_ragged_output_as_tiles_plus_edge_strips_sampled(oracle_mod, shape):
     want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, "NN", a, b, ii, jj))
     for layout in LAYOUTS:
         parts = B.plan(M, N, K, layout)
-        assert len(parts) >= 1 + (M != mm) + (N != nm) and parts[0]["variant"] != edge_variant(), parts
-        assert [p["variant"] for p in parts].count(edge_variant()) == (M != mm) + (N != nm)
+        if layout == "TN" and M % 8:
+            assert len(parts) == 1 and parts[0]["variant"] == edge_variant()   # rows of A off 16-byte boundaries
+        else:
+            assert len(parts) >= 1 + (M != mm) + (N != nm) and parts[0]["variant"] != edge_variant(), parts
+            assert [p["variant"] for p in parts].count(edge_variant()) == (M != mm) + (N != nm)
         A, Bm = store(a, b, layout)
         got = run_gpu_guard_rows("fwd", M, N, K, layout, A, Bm)
         assert np.isfinite(U.bits_to_f64(got)).all(), f"{shape} {layout}: unwritten or non-finite output"
