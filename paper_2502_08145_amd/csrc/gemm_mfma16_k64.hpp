@@ -202,15 +202,19 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         static_for<MI / 4>([&](auto d) __attribute__((always_inline)) { tie_to_lds_wait<4>(&fa[S][4 * decltype(d)::value]); });
         static_for<NI / 4>([&](auto d) __attribute__((always_inline)) { tie_to_lds_wait<4>(&fb[S][4 * decltype(d)::value]); });
     };
-    // cluster Q of NC = 4: its share of the fragment reads of a sub-step into register buffer S (A
+    // cluster Q of NC: its share of the fragment reads of a sub-step into register buffer S (A
     // blocks, then B), and of the direct loads of an iteration
-    constexpr int NC = 4, RPC = NRD / NC, LPC = NLD / NC;
+    // (measured: with two MN-contiguous operands, whose fragments take two transposing reads each, six
+    // clusters are 1.5-2 % faster than four; with K-contiguous operands it makes no difference)
+    constexpr int NC = (!A_KC && !B_KC) ? 6 : 4;
     constexpr int PB = NM / 8;                          // MFMAs before the barrier and the first cluster
-    constexpr int DP = (3 * NM / 4 - PB) / (NC - 1);    // ... between clusters
+    constexpr int R = 3 * NM / 4 - PB;                  // ... spread between the clusters; the last quarter of the
+                                                        // sub-step follows the last cluster and covers its reads' latency
     auto read_cluster = [&](auto q_c, auto s_c, const typename OpA::Cursor& ca, const typename OpB::Cursor& cb) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
-        static_for<RPC>([&](auto d) __attribute__((always_inline)) {
-            constexpr int X = RPC * Q + decltype(d)::value;
+        constexpr int RF = Q * NRD / NC, RL = (Q + 1) * NRD / NC;
+        static_for<RL - RF>([&](auto d) __attribute__((always_inline)) {
+            constexpr int X = RF + decltype(d)::value;
             if constexpr (X < MI)
                 opa.template read<X>(fa[S][X], ca);
             else
@@ -219,7 +223,8 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     };
     auto load_cluster = [&](auto q_c, uint32_t buf) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value;
-        static_for<LPC>([&](auto d) __attribute__((always_inline)) { issue(Int<LPC * Q + decltype(d)::value>{}, buf); });
+        constexpr int LF = Q * NLD / NC, LL = (Q + 1) * NLD / NC;
+        static_for<LL - LF>([&](auto d) __attribute__((always_inline)) { issue(Int<LF + decltype(d)::value>{}, buf); });
     };
 
     // ---- prologue: iterations 0 and 1 into buffers 0 and 1 -----------------------------------------
@@ -258,9 +263,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
             if constexpr (LOAD) load_cluster(q_c, cur);
             AXONN_FENCE();
             if constexpr (Q < NC - 1)
-                mfma_range(s_c, Int<PB + Q * DP>{}, Int<PB + (Q + 1) * DP>{});
+                mfma_range(s_c, Int<PB + Q * R / (NC - 1)>{}, Int<PB + (Q + 1) * R / (NC - 1)>{});
             else
-                mfma_range(s_c, Int<PB + (NC - 1) * DP>{}, Int<NM>{});
+                mfma_range(s_c, Int<PB + R>{}, Int<NM>{});
             AXONN_FENCE();
         });
         if constexpr (LOAD) advance_window();
