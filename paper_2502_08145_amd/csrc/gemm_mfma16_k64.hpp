@@ -208,8 +208,6 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     // clusters are 1.5-2 % faster than four; with K-contiguous operands it makes no difference)
     constexpr int NC = (!A_KC && !B_KC) ? 6 : 4;
     constexpr int PB = NM / 8;                          // MFMAs before the barrier and the first cluster
-    constexpr int R = 3 * NM / 4 - PB;                  // ... spread between the clusters; the last quarter of the
-                                                        // sub-step follows the last cluster and covers its reads' latency
     auto read_cluster = [&](auto q_c, auto s_c, const typename OpA::Cursor& ca, const typename OpB::Cursor& cb) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
         constexpr int RF = Q * NRD / NC, RL = (Q + 1) * NRD / NC;
@@ -242,8 +240,10 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     //   READ: fragments for the following sub-step are read (S = 0: sub-step 1 of the same buffer;
     //         S = 1: sub-step 0 of the other buffer, after the barrier).
     //   LOAD (S = 1): the iteration after next is fetched into the running buffer, after the barrier.
-    auto substep = [&](auto s_c, auto read_c, auto load_c) __attribute__((always_inline)) {
+    auto substep = [&](auto s_c, auto read_c, auto load_c, auto phase_c) __attribute__((always_inline)) {
         constexpr int S = decltype(s_c)::value;
+        constexpr int P0 = PB + (decltype(phase_c)::value ? NM / 8 : 0);   // MFMAs before the first cluster
+        constexpr int R = 3 * NM / 4 - P0;
         constexpr bool READ = decltype(read_c)::value, LOAD = decltype(load_c)::value;
         static_assert(!LOAD || (S == 1 && READ), "loads go out in sub-step 1 of an iteration that has a successor");
         wait_fragments(s_c);
@@ -257,15 +257,19 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
             __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffer is free
             AXONN_FENCE();
         }
+        if constexpr (P0 > PB) {
+            mfma_range(s_c, Int<PB>{}, Int<P0>{});
+            AXONN_FENCE();
+        }
         static_for<NC>([&](auto q_c) __attribute__((always_inline)) {
             constexpr int Q = decltype(q_c)::value;
             if constexpr (READ) read_cluster(q_c, Int<1 - S>{}, ca, cb);
             if constexpr (LOAD) load_cluster(q_c, cur);
             AXONN_FENCE();
             if constexpr (Q < NC - 1)
-                mfma_range(s_c, Int<PB + Q * R / (NC - 1)>{}, Int<PB + (Q + 1) * R / (NC - 1)>{});
+                mfma_range(s_c, Int<P0 + Q * R / (NC - 1)>{}, Int<P0 + (Q + 1) * R / (NC - 1)>{});
             else
-                mfma_range(s_c, Int<PB + R>{}, Int<NM>{});
+                mfma_range(s_c, Int<P0 + R>{}, Int<NM>{});
             AXONN_FENCE();
         });
         if constexpr (LOAD) advance_window();
@@ -274,21 +278,35 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     using Yes = std::true_type;
     using No = std::false_type;
 
-    // fragments of iteration 0, sub-step 0
-    {
-        const typename OpA::Cursor ca = opa.template cursor<0>(0u);
-        const typename OpB::Cursor cb = opb.template cursor<0>(0u);
-        static_for<NC>([&](auto q_c) __attribute__((always_inline)) { read_cluster(q_c, Int<0>{}, ca, cb); });
-    }
     const int KI = ktotal / Cfg::KS;   // at least 2
-    for (int it = KI - 2; it > 0; --it) {
-        substep(Int<0>{}, Yes{}, No{});
-        substep(Int<1>{}, Yes{}, Yes{});
+    auto run = [&](auto phase_c) __attribute__((always_inline)) {
+        // fragments of iteration 0, sub-step 0 (inside the phase's own code path: no join between a read and its wait)
+        {
+            const typename OpA::Cursor ca = opa.template cursor<0>(0u);
+            const typename OpB::Cursor cb = opb.template cursor<0>(0u);
+            static_for<NC>([&](auto q_c) __attribute__((always_inline)) { read_cluster(q_c, Int<0>{}, ca, cb); });
+        }
+        for (int it = KI - 2; it > 0; --it) {
+            substep(Int<0>{}, Yes{}, No{}, phase_c);
+            substep(Int<1>{}, Yes{}, Yes{}, phase_c);
+        }
+        substep(Int<0>{}, Yes{}, No{}, phase_c);   // iteration KI-2: nothing left to fetch
+        substep(Int<1>{}, Yes{}, No{}, phase_c);
+        substep(Int<0>{}, Yes{}, No{}, phase_c);   // iteration KI-1
+        substep(Int<1>{}, No{}, No{}, phase_c);
+    };
+    // With two waves per SIMD the second one (waves 4-7) can issue its clusters an eighth of a sub-step
+    // later, so that one wave's reads and loads fall into the other's MFMA runs.  Measured on the
+    // benchmark's NT product without split-K: 205 -> 196 us.  It takes a second copy of the loop, and in
+    // every other instantiation that copy makes the register allocator spill (TN 199 -> 222 us, NN with two
+    // K ranges 210 -> 262), so it is used where it fits only.
+    constexpr bool PHASED = NW == 8 && A_KC && B_KC && !SPLITK;
+    if constexpr (PHASED) {
+        if (wave >= 4) run(Int<1>{});   // wave-uniform; both paths hit the same barriers
+        else run(Int<0>{});
+    } else {
+        run(Int<0>{});
     }
-    substep(Int<0>{}, Yes{}, No{});   // iteration KI-2: nothing left to fetch
-    substep(Int<1>{}, Yes{}, No{});
-    substep(Int<0>{}, Yes{}, No{});   // iteration KI-1
-    substep(Int<1>{}, No{}, No{});
     __syncthreads();   // every wave is done with the buffers before the epilogue reuses LDS
 
     if constexpr (SPLITK) {
