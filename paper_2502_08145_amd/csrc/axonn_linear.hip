@@ -293,10 +293,14 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     constexpr double kFixedK = 128.0;
     const Variant& var = g_variants[v];
     if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) return -1.0;
-    // the 64-k kernels hold two K-steps less in LDS than the 32-k ring; over very long K ranges the
-    // workgroups behind one L2 drift further apart than that tolerates (measured: ahead of the 32-k
-    // kernels up to K = 24576 in one range and up to K = 32768 split, 2-14 % behind beyond)
-    if ((var.base == 14 || var.base == 15) && (K > 32768 || (var.splits == 1 && K > 24576))) return -1.0;
+    // The 64-k kernels hold two K-steps less in LDS than the 32-k ring; over very long K ranges the
+    // workgroups behind one L2 drift further apart than that tolerates.  Measured with the final
+    // epilogue: in NT the 64-k kernel is 4-5 % behind the ring at K = 32768 and 49152 (8192 x 8192
+    // outputs) and ahead of it up to 24576; in NN and TN it stays 1-5 % ahead at those K.  The split-K
+    // forms were compared up to K = 32768 only.
+    if (var.base == 14 || var.base == 15) {
+        if (var.splits == 1 ? (layout == AXONN_NT && K > 24576) : K > 32768) return -1.0;
+    }
     const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
     // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
     // side by side at half speed each, which comes to the same).  A last round that fills only
