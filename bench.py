@@ -68,17 +68,17 @@ def bench_transpose(args):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in shapes]
-          for _ in range(args.steps)]
+    # one event before the first transpose of a step and one after every transpose (see main)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(shapes) + 1)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for s_i in range(args.steps):
+        ev[s_i][0].record(stream)
         for i, ((r, c), s_, d_) in enumerate(zip(shapes, src, dst)):
-            ev[s_i][i][0].record(stream)
             B.axonn_transpose_bf16(r, c, s_, d_, stream)
-            ev[s_i][i][1].record(stream)
+            ev[s_i][i + 1].record(stream)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    per = [float(np.mean([ev[s_i][i][0].elapsed_time(ev[s_i][i][1]) for s_i in range(args.steps)])) for i in range(len(shapes))]
+    per = [float(np.mean([ev[s_i][i].elapsed_time(ev[s_i][i + 1]) for s_i in range(args.steps)])) for i in range(len(shapes))]
     for (r, c), ms in zip(shapes, per):
         log(f"  transpose [{r:>6d},{c:>6d}]  {ms * 1e3:8.1f} us  {4.0 * r * c / ms / 1e6:7.0f} GB/s")
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
@@ -193,17 +193,18 @@ def main():
             launch(g, w % sets)
     torch.cuda.synchronize()
 
-    # ---- timed region: K steps; every launch bracketed by HIP events on the launch stream --
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in gemms]
-          for _ in range(args.steps)]
+    # ---- timed region: K steps; HIP events on the launch stream before the first GEMM of a step and after
+    # every GEMM, so that GEMM i runs between events i and i+1.  (An event record costs about 3 us of
+    # stream time on this part: a pair of events of its own around every launch made the step 2 % longer
+    # than this, and with no events at all it would be another 1.5 % shorter.)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(gemms) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
+        ev[s][0].record(stream)
         for gi, g in enumerate(gemms):
-            e0, e1 = ev[s][gi]
-            e0.record(stream)
             launch(g, s % sets)
-            e1.record(stream)
+            ev[s][gi + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -211,7 +212,7 @@ def main():
 
     per = []
     for gi, g in enumerate(gemms):
-        ms = float(np.mean([ev[s][gi][0].elapsed_time(ev[s][gi][1]) for s in range(args.steps)]))
+        ms = float(np.mean([ev[s][gi].elapsed_time(ev[s][gi + 1]) for s in range(args.steps)]))
         per.append(ms)
         alg_bytes = 2.0 * (g["M"] * g["K"] + g["K"] * g["N"] + g["M"] * g["N"])   # A, B read once, C written once
         log(f"  {g['name']:<22s} {g['layout']} M={g['M']:<6d} N={g['N']:<6d} K={g['K']:<6d} {g['variant']:<40s} "
