@@ -18,11 +18,12 @@
 //    landed (vmcnt(0)): those of iteration i+1, issued one iteration earlier, i.e. a lead of
 //    almost two sub-steps.
 //
-// Measured: with eight waves it is the fastest kernel for NN and NT (3-4 % over the 32-k kernel in
-// the benchmark step, more for the split-K forms); with four waves it wins only for NT without
-// split-K, by a hair; TN ties or loses, so TN stays with gemm_tile_kernel16.  Fragments, MFMA order
-// (mfma(Bfrag, Afrag)), accumulator layout, split-K exchange, epilogue and the XCD-aware tile order
-// are those of gemm_tile_kernel16.
+// Measured: with eight waves it is the fastest kernel in all three modes (NN and NT: 3-4 % over the
+// 32-k kernel in the benchmark step, more for the split-K forms; TN: 2-4 % since C is streamed out as
+// non-temporal stores, with the reads and loads of a sub-step cut into six clusters instead of four);
+// the 32-k ring keeps NT at K above 24576 and TN with four and more K ranges.  With four waves it wins
+// only for NT without split-K, by a hair.  Fragments, MFMA order (mfma(Bfrag, Afrag)), accumulator
+// layout, split-K exchange, epilogue and the XCD-aware tile order are those of gemm_tile_kernel16.
 #pragma once
 #include "gemm_mfma16.hpp"
 
