@@ -168,6 +168,38 @@ __device__ __forceinline__ void store_tile16(f32x4 (&acc)[MI][NI], uint8_t* smem
     }
 }
 
+// One block row of a wave tile (16 rows x TN columns, acc[i][0..NI)) to C at `pc_row`, converted and
+// transposed like store_tile16 does it, through a region of 16 * TN * 2 bytes at `epi` that belongs to
+// this wave alone.  The region may be reused for the next block row straight away: a wave's LDS
+// operations execute in order, so the next staging writes cannot overtake these reads.
+template <int TN, int NI>
+__device__ __forceinline__ void store_block_row16(f32x4 (&row)[NI], uint8_t* epi, uint16_t* pc_row, int ldc, int lane) {
+    constexpr int CPR = TN / 8;
+    constexpr uint32_t CMASK = CPR - 1;
+    const uint32_t quad = lane >> 4, r16 = lane & 15;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const uint32_t chunk = j * 2 + (quad >> 1);
+        u32x2 v;
+        v[0] = pack2_bf16(row[j][0], row[j][1]);
+        v[1] = pack2_bf16(row[j][2], row[j][3]);
+        *reinterpret_cast<u32x2*>(epi + r16 * (TN * 2) + ((chunk ^ (r16 & CMASK)) << 4) + (quad & 1) * 8) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int it = 0; it < (16 * CPR) / 64; ++it) {
+        const uint32_t idx = it * 64 + lane;
+        const uint32_t r = idx / CPR, ch = idx % CPR;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + r * (TN * 2) + ((ch ^ (r & CMASK)) << 4));
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(pc_row + (int64_t)r * ldc + ch * 8));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Requires M % BM == 0, N % BN == 0, K % 64 == 0, K >= TileCfg16::MIN_K (per K range when split).
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, bool SPLITK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
