@@ -124,8 +124,9 @@ def main():
     ap.add_argument("--tune", action="store_true",
                     help="after the timed region, run the mode tuner on every GEMM of the workload and log its table")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
-                    help="before the timed region, run plain device copies of this many MiB (a kernel of known "
-                         "HBM traffic, used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+                    help="before the timed region, transpose a matrix of this many MiB three times (a kernel of "
+                         "exactly known HBM traffic: every element read once and written once; used to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding across GPUs); "
@@ -146,6 +147,7 @@ def main():
     B.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    B.register_workspace()   # the library allocates nothing: its split-K kernels use this torch-owned area
 
     def up(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
@@ -173,14 +175,15 @@ def main():
         f"operands and outputs per step, {sets} operand set(s) used in turn")
 
     if args.calibrate_copy > 0:
-        n = args.calibrate_copy * (1 << 20) // 2
-        src = torch.empty(n, dtype=torch.bfloat16, device=dev).normal_()
-        dst = torch.empty_like(src)
+        rows = 8192
+        cols = args.calibrate_copy * (1 << 20) // 2 // rows
+        src = torch.empty((rows, cols), dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty((cols, rows), dtype=torch.bfloat16, device=dev)
         for _ in range(3):          # each reads and writes calibrate_copy MiB
-            B.axonn_linear_copy_probe(src, dst, n * 2, torch.cuda.current_stream())
+            B.axonn_transpose_bf16(rows, cols, src, dst, torch.cuda.current_stream())
         torch.cuda.synchronize()
-        assert torch.equal(dst.view(torch.int16), src.view(torch.int16))
-        log(f"copy calibration: 3 device copies of {args.calibrate_copy} MiB")
+        assert torch.equal(dst.view(torch.int16), src.view(torch.int16).t())
+        log(f"traffic calibration: 3 transposes of a {rows} x {cols} matrix ({args.calibrate_copy} MiB)")
         del src, dst
 
     stream = torch.cuda.current_stream()
@@ -233,36 +236,26 @@ def main():
         d["ms"] += ms; d["flops"] += g["flops"]; d["n"] += 1
     dom = max(groups, key=lambda k: groups[k]["ms"])
     achieved = groups[dom]["flops"] / groups[dom]["ms"] / 1e9
-    traffic = None
+    # HBM bytes per launch of that kernel from the stored rocprofv3 counter runs -- only if they were
+    # taken with the kernel sources this run uses (else null: a stale reading is worse than none)
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
+            from paper_2502_08145_amd.build import source_id
             from paper_2502_08145_amd.profile_summary import kernel_key
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(kernel_key(*dom.split("/")))
+            stored = json.load(open(tpath))
+            if stored.get("_source") == source_id():
+                traffic = stored.get(args.workload, {}).get(kernel_key(*dom.split("/")))
+                traffic_source = stored.get("_source")
         except Exception:
             traffic = None
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "kernel": dom,
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                "kernel": dom,
                 "launches_per_step": groups[dom]["n"],
                 "mean_launch_us": round(groups[dom]["ms"] / groups[dom]["n"] * 1e3, 2),
                 "flops_per_launch": groups[dom]["flops"] / groups[dom]["n"]}
-
-    # ---- context: what the matrix pipes sustain on these operand values with no data movement ----
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    pdata = gemms[0]["a"][0].reshape(-1)[: 1 << 20]          # N(0,1) activations of the first layer
-    sink = torch.zeros(1, dtype=torch.float32, device=dev)
-    iters = 4000
-    for _ in range(100):      # half a second: the clock settles to what the power limit allows this kernel
-        B.axonn_linear_mfma_probe(pdata, iters, cus, sink, stream)
-    torch.cuda.synchronize()
-    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    p0.record(stream)
-    for _ in range(10):
-        B.axonn_linear_mfma_probe(pdata, iters, cus, sink, stream)
-    p1.record(stream)
-    torch.cuda.synchronize()
-    probe_tflops = cus * 4 * iters * 64 * 32768.0 * 10 / (p0.elapsed_time(p1) * 1e-3) / 1e12
-    log(f"MFMA-only probe on the same N(0,1) values: {probe_tflops:.1f} TFLOP/s ({cus} CUs, registers only, steady state)")
 
     # ---- context: board power and shader clock while the step runs (the published peak assumes 2.4 GHz) ----
     board = None
@@ -340,7 +333,7 @@ def main():
            "config": {"workload": args.workload, "gemms": len(gemms), "layouts": "natural (fwd NN, bwd_data NT, bwd_weight TN)",
                       "step_tflop": round(step_flops / 1e12, 4), "operand_sets": sets},
            "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
-           "mfma_only_probe_tflops": round(probe_tflops, 1), "board": board,
+           "board": board,
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 

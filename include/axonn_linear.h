@@ -36,18 +36,21 @@
  *              packed, 16-byte aligned.  The caller owns all three buffers; the
  *              library keeps no reference after return and never reads the
  *              output.  The output must not overlap an input.
- *   scratch    outputs of few tiles and long K are computed by split-K kernels,
- *              which exchange fp32 partial tiles through a scratch area owned by
- *              the library: 64 MiB of device memory per GPU, allocated (hipMalloc)
- *              by axonn_linear_init or by the first call that needs it, and kept
- *              until the process ends -- or memory of the caller's, registered with
- *              axonn_linear_set_workspace, in which case the library never
- *              allocates.  If no area can be had the other kernels run.
+ *   scratch    outputs of few tiles and long K are computed fastest by split-K kernels,
+ *              which exchange fp32 partial tiles through a scratch area.  The library
+ *              allocates NO device memory: the area is memory of the caller's,
+ *              registered per GPU with axonn_linear_set_workspace (size it with
+ *              axonn_linear_workspace_bytes; 4 KiB + 64 MiB covers every product).
+ *              Without a registered area, or for a product that needs a larger one,
+ *              the kernels that need no scratch run (same result to the last bit is
+ *              NOT promised between the two: the summation order differs).
  *              Calls that may EXECUTE CONCURRENTLY on one GPU (different streams)
- *              would share it: serialise them or switch split-K off
- *              (axonn_linear_set_split_k).  Calls on one stream are always safe.
+ *              would share the area and corrupt each other's partial sums: serialise
+ *              them or switch split-K off (axonn_linear_set_split_k).  Calls on one
+ *              stream are always safe.
  *   stream     a hipStream_t passed as void*; NULL is the default stream.  The
- *              call enqueues work and returns; it never synchronises.
+ *              call enqueues work and returns; it never synchronises and never
+ *              allocates, so it may be captured into a HIP graph and replayed.
  *   fp32_accumulate
  *              1: fp32 accumulators over all of K, one rounding at the store.
  *              0: the caller does not require fp32; the same kernels run (the
@@ -86,7 +89,7 @@ enum {
     AXONN_ERR_INVALID_ARG = -1, /* null / misaligned pointer, negative or oversized dim, bad enum or flag */
     AXONN_ERR_UNSUPPORTED = -2, /* a forced kernel variant cannot run this shape */
     AXONN_ERR_LAUNCH = -3,      /* the HIP runtime refused the launch */
-    AXONN_ERR_WORKSPACE = -4    /* a forced split-K variant has no scratch area (allocation failed / workspace too small) */
+    AXONN_ERR_WORKSPACE = -4    /* a forced split-K variant has no registered scratch area, or too small a one */
 };
 
 /* Forward, Algorithm 1 line 3:  Y[M,N] = X * W.  X and W stored as `layout` says. */
@@ -150,7 +153,7 @@ int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_resul
 /* Forget all remembered results. */
 void axonn_linear_tune_reset(void);
 
-/* ---- communication performance model (Sec. V-A, Eq. 1-7); host only, no GPU is touched -------- */
+/* ---- communication performance model (Sec. IV-B, Eq. 1-7); host only, no GPU is touched -------- */
 
 /* One FC layer: an m x k input batch times a k x n weight (global sizes, before any sharding);
  * transposed != 0 for the layers whose weight is stored 'transposed', for which the X and Y process
@@ -195,31 +198,32 @@ const char *axonn_status_string(int status);
 /* Library version, major * 10000 + minor * 100 + patch. */
 int axonn_linear_version(void);
 
-/* Caller-owned split-K scratch.  axonn_linear_workspace_bytes: what the kernel the library would
- * pick for this problem needs (0: none).  axonn_linear_set_workspace: use `bytes` bytes at the
+/* Caller-owned split-K scratch.  axonn_linear_workspace_bytes: what the launches the library would
+ * make for this problem need (0: none; otherwise at least the 4 KiB + 256 KiB that
+ * axonn_linear_set_workspace accepts).  axonn_linear_set_workspace: use `bytes` bytes at the
  * DEVICE pointer `dev_ptr` (256-byte aligned) as the current device's scratch area from now on; the
- * first 4 KiB are cleared (synchronously).  The caller keeps ownership and must keep the memory
- * alive, and untouched, while it is registered; NULL / 0 unregisters it.  A problem whose need
- * exceeds the registered size runs without split-K.  Must not be called while GEMM calls are in
+ * first 4 KiB are cleared (hipMemset, then a device synchronisation: this call is synchronous).  The
+ * caller keeps ownership and must keep the memory alive, and untouched, while it is registered;
+ * NULL / 0 unregisters it.  A problem whose need exceeds the registered size, and every problem
+ * while nothing is registered, runs without split-K.  Must not be called while GEMM calls are in
  * flight on that device.  AXONN_OK, AXONN_ERR_INVALID_ARG, or AXONN_ERR_WORKSPACE if `bytes` cannot
- * hold a single tile (4 KiB + 256 KiB). */
+ * hold a single tile (4 KiB + 256 KiB) or the area could not be cleared. */
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout);
 int axonn_linear_set_workspace(void *dev_ptr, size_t bytes);
 
-/* Optional set-up for the current device: raises the kernels' LDS limits and allocates the split-K
- * scratch area now rather than inside the first call that needs it (do this before capturing calls
- * into a HIP graph: an allocation is not allowed during capture; captured calls, split-K ones
- * included, may be replayed any number of times on one stream).  Idempotent.  AXONN_OK, or
- * AXONN_ERR_WORKSPACE if the allocation failed (the library then works without split-K). */
+/* Optional set-up for the current device: raises the kernels' LDS limits now rather than inside the
+ * first GEMM call (hipFuncSetAttribute; no device memory is allocated, nothing is launched).
+ * Idempotent.  Returns AXONN_OK. */
 int axonn_linear_init(void);
 
 /* Allow (1, the default) or forbid (0) the automatic choice of split-K kernels, process-wide.
  * Returns the previous setting, or AXONN_ERR_INVALID_ARG. */
 int axonn_linear_set_split_k(int enable);
 
-/* Diagnostics: how many times, on the current device, a split-K workgroup gave up waiting for a
- * partial tile (it waits about a second; this cannot happen unless another workgroup of the same
- * launch died).  Synchronous device-to-host copy.  *count is 0 when no split-K kernel has run. */
+/* Diagnostics: how many times, in the scratch area now registered on the current device, a split-K
+ * workgroup gave up waiting for a partial tile (it waits about a second; this cannot happen unless
+ * another workgroup of the same launch died).  Synchronous device-to-host copy.  *count is 0 when
+ * no area is registered. */
 int axonn_linear_split_k_timeouts(uint64_t *count);
 
 /* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any
@@ -251,25 +255,13 @@ typedef struct {
     int64_t m, n, row0, col0;
 } axonn_plan_part_t;
 int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[AXONN_MAX_PLAN_PARTS]);
+/* The same for a call made NOW on the current device: as axonn_linear_plan unless the plan needs a
+ * larger scratch area than the one registered there (or none is registered), in which case it is
+ * the plan without split-K that the call would fall back to.  Host logic plus one hipGetDevice. */
+int axonn_linear_call_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[AXONN_MAX_PLAN_PARTS]);
 /* Override the choice for all later calls in this process; -1 restores automatic selection.
  * Returns AXONN_OK or AXONN_ERR_INVALID_ARG.  For tests, tuning and the benchmark. */
 int axonn_linear_force_variant(int variant);
-
-/* Measurement aid: enqueue a plain device copy of `bytes` bytes (a multiple of 16; both DEVICE
- * pointers 16-byte aligned, not overlapping) on `stream`.  Its HBM traffic is exactly `bytes` read
- * and `bytes` written, which is what profiler byte counters are scaled against.  Returns AXONN_OK,
- * AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
-int axonn_linear_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
-
-/* Measurement aid: the matrix-pipe ceiling for a given operand distribution.  Launches
- * `workgroups` workgroups of 4 waves; every wave reads 32 operand fragments once from `data`
- * (DEVICE pointer, 16-byte aligned, at least 128 KiB of bf16 values, the same for all workgroups)
- * and then issues iters * 128 bf16 MFMAs (16x16x32, the instruction of the default tile kernels) on
- * registers only: iters * 64 * 32768 flops per wave, no memory traffic.  `sink` is a DEVICE pointer to one float (never written in practice).
- * Time it with events; with one workgroup per compute unit this is what the kernels above could
- * reach if operands were free.  Returns AXONN_OK, AXONN_ERR_INVALID_ARG or AXONN_ERR_LAUNCH. */
-int axonn_linear_mfma_probe(const void *data, size_t data_bytes, int iters, int workgroups,
-                            void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -1,6 +1,6 @@
 """Plain Python statement of the paper's communication performance model (TEST INFRASTRUCTURE ONLY).
 
-Sec. V-A of the paper ("performance model" subsection): ring collectives, start-up costs ignored,
+Sec. IV-B of the paper ("performance model" subsection): ring collectives, start-up costs ignored,
 so a collective's time is (bytes each process sends) / (bandwidth of its process group).
 
 * layer_comm_time   Eq. 1-5 (the five collectives of one FC layer with an m x k input batch and a

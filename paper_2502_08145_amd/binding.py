@@ -23,8 +23,8 @@ EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
-    "axonn_linear_plan",
-    "axonn_linear_force_variant", "axonn_linear_copy_probe", "axonn_linear_mfma_probe",
+    "axonn_linear_plan", "axonn_linear_call_plan",
+    "axonn_linear_force_variant",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
     "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
     "axonn_linear_tune", "axonn_linear_tuned", "axonn_linear_tune_reset",
@@ -100,12 +100,10 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_select_variant.restype = ci
         L.axonn_linear_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(PlanPart)]
         L.axonn_linear_plan.restype = ci
+        L.axonn_linear_call_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(PlanPart)]
+        L.axonn_linear_call_plan.restype = ci
         L.axonn_linear_force_variant.argtypes = [ci]
         L.axonn_linear_force_variant.restype = ci
-        L.axonn_linear_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
-        L.axonn_linear_copy_probe.restype = ci
-        L.axonn_linear_mfma_probe.argtypes = [vp, ctypes.c_size_t, ci, ci, vp, vp]
-        L.axonn_linear_mfma_probe.restype = ci
         L.axonn_linear_workspace_bytes.argtypes = [i64, i64, i64, ci]
         L.axonn_linear_workspace_bytes.restype = ctypes.c_size_t
         L.axonn_linear_set_workspace.argtypes = [vp, ctypes.c_size_t]
@@ -174,9 +172,19 @@ def plan(M: int, N: int, K: int, layout) -> list:
     return [dict(variant=p.variant, m=p.m, n=p.n, row0=p.row0, col0=p.col0) for p in parts[:n]]
 
 
-def plan_name(M: int, N: int, K: int, layout) -> str:
-    """Variant names of the launches of plan(), joined by '+'."""
-    return "+".join(variant_name(p["variant"]) for p in plan(M, N, K, layout))
+def call_plan(M: int, N: int, K: int, layout) -> list:
+    """plan() for a call made now on the current device: without split-K if the registered scratch
+    area is missing or too small for it."""
+    parts = (PlanPart * MAX_PLAN_PARTS)()
+    n = lib().axonn_linear_call_plan(M, N, K, _layout(layout), parts)
+    if n < 0:
+        raise AxonnError(n, "axonn_linear_call_plan")
+    return [dict(variant=p.variant, m=p.m, n=p.n, row0=p.row0, col0=p.col0) for p in parts[:n]]
+
+
+def plan_name(M: int, N: int, K: int, layout, now: bool = False) -> str:
+    """Variant names of the launches of plan() (now=True: of call_plan()), joined by '+'."""
+    return "+".join(variant_name(p["variant"]) for p in (call_plan if now else plan)(M, N, K, layout))
 
 
 def force_variant(v: int) -> None:
@@ -186,7 +194,7 @@ def force_variant(v: int) -> None:
 
 
 def axonn_linear_init() -> None:
-    """Set up the current device (LDS limits, split-K scratch area) ahead of the first call."""
+    """Set up the current device (kernel LDS limits) ahead of the first call."""
     rc = lib().axonn_linear_init()
     if rc != 0:
         raise AxonnError(rc, "axonn_linear_init")
@@ -209,6 +217,28 @@ def axonn_linear_set_workspace(buf, check=True) -> int:
     if check and rc != 0:
         raise AxonnError(rc, "axonn_linear_set_workspace")
     return rc
+
+
+WORKSPACE_ALL = 4096 + 256 * 256 * 256 * 4   # flags + 256 slots of one 256 x 256 fp32 tile: enough for every product
+
+_workspace = {}   # device index -> the tensor registered by register_workspace (kept alive here)
+
+
+def register_workspace(nbytes: int = WORKSPACE_ALL):
+    """Allocate `nbytes` of device memory through torch on the current device and register it as that
+    device's split-K scratch area (the library itself allocates nothing).  Returns the tensor; it is
+    kept alive until unregister_workspace() or the end of the process."""
+    dev = torch.cuda.current_device()
+    buf = torch.empty((int(nbytes),), dtype=torch.uint8, device=f"cuda:{dev}")
+    axonn_linear_set_workspace(buf)
+    _workspace[dev] = buf
+    return buf
+
+
+def unregister_workspace() -> None:
+    torch.cuda.synchronize()
+    axonn_linear_set_workspace(None)
+    _workspace.pop(torch.cuda.current_device(), None)
 
 
 def axonn_linear_set_split_k(enable: bool) -> bool:
@@ -350,23 +380,6 @@ def axonn_comm_rank_grids(g_total, layers, g_node, beta_inter, intra_db, bytes_p
     if rc < 0:
         raise AxonnError(int(rc), "axonn_comm_rank_grids")
     return [(out[i].seconds, (out[i].gx, out[i].gy, out[i].gz, out[i].gdata)) for i in range(n)]
-
-
-def axonn_linear_copy_probe(src, dst, nbytes, stream=None, check=True):
-    """Plain device copy of nbytes (known HBM traffic: nbytes read + nbytes written)."""
-    rc = lib().axonn_linear_copy_probe(_ptr(src), _ptr(dst), int(nbytes), _stream(stream))
-    if check and rc != AXONN_OK:
-        raise AxonnError(rc, "axonn_linear_copy_probe")
-    return rc
-
-
-def axonn_linear_mfma_probe(data, iters, workgroups, sink, stream=None, check=True):
-    """Registers-only MFMA loop on the operand values in `data` (bf16 tensor, >= 128 KiB)."""
-    rc = lib().axonn_linear_mfma_probe(_ptr(data), data.numel() * 2, int(iters), int(workgroups), sink.data_ptr(),
-                                       _stream(stream))
-    if check and rc != AXONN_OK:
-        raise AxonnError(rc, "axonn_linear_mfma_probe")
-    return rc
 
 
 OPS = {"fwd": axonn_linear_fwd, "bwd_data": axonn_linear_bwd_data, "bwd_weight": axonn_linear_bwd_weight}

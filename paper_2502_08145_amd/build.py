@@ -31,6 +31,19 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found (looked at $HIPCC, PATH and /opt/rocm/bin)")
 
 
+def source_id() -> str:
+    """Short hash of the kernel sources (csrc/ and the C header): names the build a measurement was
+    taken with, so that a stored counter reading can be told from one of an older kernel."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc")))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "axonn_linear.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def build(verbose: bool = False, extra=()) -> str:
     os.makedirs(LIB_DIR, exist_ok=True)
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, SRC, "-o", LIB]

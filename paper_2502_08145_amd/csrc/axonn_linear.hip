@@ -1,6 +1,8 @@
 // C ABI of the FC-layer GEMM library (see include/axonn_linear.h for the contract).
-// Host side: argument checks, kernel-variant selection, launch.  No device memory is
-// allocated here and nothing synchronises.
+// Host side: argument checks, kernel-variant selection, launch.  No device memory is allocated
+// anywhere in this file, and the GEMM entry points never synchronise: split-K kernels exchange their
+// partial tiles through memory the caller registered (axonn_linear_set_workspace, which clears the
+// flag words synchronously).
 #include "../../include/axonn_linear.h"
 
 #include <hip/hip_runtime.h>
@@ -29,64 +31,20 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const uint16_t* __restr
                                                          const uint16_t* __restrict__ B,
                                                          uint16_t* __restrict__ C, int64_t M,
                                                          int64_t N, int64_t K) {
-    const int64_t j = (int64_t)blockIdx.x * 16 + (threadIdx.x & 15);
-    const int64_t i = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
-    if (i >= M || j >= N) return;
-    float acc = 0.f;
-    for (int64_t k = 0; k < K; ++k) {
-        const uint16_t a = (LAYOUT == AXONN_TN) ? A[k * M + i] : A[i * K + k];
-        const uint16_t b = (LAYOUT == AXONN_NT) ? B[j * K + k] : B[k * N + j];
-        acc += __builtin_bit_cast(float, (uint32_t)a << 16) * __builtin_bit_cast(float, (uint32_t)b << 16);
+    // 16 x 16 output blocks, numbered row-major, dealt out to the workgroups of a 1-D grid in turn
+    const int64_t blocks_n = (N + 15) / 16, blocks = ((M + 15) / 16) * blocks_n;
+    for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
+        const int64_t j = (blk % blocks_n) * 16 + (threadIdx.x & 15);
+        const int64_t i = (blk / blocks_n) * 16 + (threadIdx.x >> 4);
+        if (i >= M || j >= N) continue;
+        float acc = 0.f;
+        for (int64_t k = 0; k < K; ++k) {
+            const uint16_t a = (LAYOUT == AXONN_TN) ? A[k * M + i] : A[i * K + k];
+            const uint16_t b = (LAYOUT == AXONN_NT) ? B[j * K + k] : B[k * N + j];
+            acc += __builtin_bit_cast(float, (uint32_t)a << 16) * __builtin_bit_cast(float, (uint32_t)b << 16);
+        }
+        C[i * N + j] = (uint16_t)(pack2_bf16(acc, 0.f) & 0xFFFFu);
     }
-    C[i * N + j] = (uint16_t)(pack2_bf16(acc, 0.f) & 0xFFFFu);
-}
-
-// Plain copy of `n16` 16-byte words: a kernel of exactly known HBM traffic (n16 * 16 bytes read and
-// as many written), used to calibrate profiler byte counters.
-__global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
-                                                         size_t n16) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-// Nothing but MFMAs: every wave keeps 16 + 16 operand fragments (read once from `data`) and 64
-// accumulator blocks in registers and issues `iters` x 128 v_mfma_f32_16x16x32_bf16, in the same
-// operand pattern as the 256x256 tile kernel on 16x16x32 MFMAs (8 A x 8 B fragments per K-step).  It measures the
-// matrix-pipe ceiling for a given operand distribution: on MI355X the sustained clock, and with it
-// this ceiling, depends on how much the operand bits toggle.
-__global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict__ data, float* __restrict__ sink,
-                                                         int iters) {
-    typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
-    bf16x8 a[16], b[16];   // two K-steps' worth of 8 + 8 fragments of 16 rows x 32 k
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        a[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * i]);
-        b[i] = __builtin_bit_cast(bf16x8, data[threadIdx.x + 256 * (16 + i)]);
-    }
-    probe_f32x4 acc[64];
-#pragma unroll
-    for (int i = 0; i < 64; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int it = 0; it < iters; ++it) {
-        // eight MFMAs per asm statement (one A fragment against the eight B fragments of its K-step):
-        // a clean issue stream, accumulators pinned in AGPRs
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                asm volatile(
-                    "v_mfma_f32_16x16x32_bf16 %0, %8, %16, %0\n\tv_mfma_f32_16x16x32_bf16 %1, %9, %16, %1\n\t"
-                    "v_mfma_f32_16x16x32_bf16 %2, %10, %16, %2\n\tv_mfma_f32_16x16x32_bf16 %3, %11, %16, %3\n\t"
-                    "v_mfma_f32_16x16x32_bf16 %4, %12, %16, %4\n\tv_mfma_f32_16x16x32_bf16 %5, %13, %16, %5\n\t"
-                    "v_mfma_f32_16x16x32_bf16 %6, %14, %16, %6\n\tv_mfma_f32_16x16x32_bf16 %7, %15, %16, %7"
-                    : "+a"(acc[i * 8 + 0]), "+a"(acc[i * 8 + 1]), "+a"(acc[i * 8 + 2]), "+a"(acc[i * 8 + 3]),
-                      "+a"(acc[i * 8 + 4]), "+a"(acc[i * 8 + 5]), "+a"(acc[i * 8 + 6]), "+a"(acc[i * 8 + 7])
-                    : "v"(b[s * 8 + 0]), "v"(b[s * 8 + 1]), "v"(b[s * 8 + 2]), "v"(b[s * 8 + 3]), "v"(b[s * 8 + 4]),
-                      "v"(b[s * 8 + 5]), "v"(b[s * 8 + 6]), "v"(b[s * 8 + 7]), "v"(a[s * 8 + i]));
-    }
-    float t = 0.f;
-#pragma unroll
-    for (int i = 0; i < 64; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-    if (t == 12345.678f) sink[0] = t;   // keeps the accumulators live; practically never taken
 }
 
 // ------------------------------------------------------------------------------------------
@@ -195,9 +153,9 @@ constexpr int kEdgeVariant = kNumVariants - 1;
 static bool is_guarded(int v) { return g_variants[v].bm == 0 || g_variants[v].edge; }
 
 // Split-K scratch: one area per device.  Layout: kFlagBytes of flags (one 32-bit flag per slot, the
-// time-out counter in the last word), then `slots` slots of one 256x256 fp32 tile.  Either the
-// caller's (axonn_linear_set_workspace) or the library's own, allocated on first need and kept until
-// the process ends.
+// time-out counter in the last word), then slots of one 256x256 fp32 tile each.  The area is the
+// caller's (axonn_linear_set_workspace); without one the three GEMM entry points run the kernels that
+// need none.  The library itself allocates nothing.
 constexpr int kScratchSlots = 256;                          // the most any variant is allowed to need
 constexpr size_t kSlotBytes = 256 * 256 * sizeof(float);
 constexpr size_t kFlagBytes = 4096;                         // 1023 flags + the counter
@@ -207,7 +165,6 @@ struct Scratch {
     float* partials = nullptr;
     uint32_t* flags = nullptr;
     size_t partial_bytes = 0;       // capacity behind `partials`
-    void* owned = nullptr;          // the library's own allocation, if it made one
     uint32_t* timeouts() const { return flags + kFlagBytes / sizeof(uint32_t) - 1; }
 };
 static Scratch g_scratch[kMaxDevices];
@@ -215,39 +172,25 @@ static std::mutex g_scratch_mutex;
 static std::atomic<uint32_t> g_epoch{0};
 static std::atomic<int> g_split_k_enabled{1};
 
-static bool adopt(Scratch& sc, void* p, size_t bytes) {
-    if (bytes < kFlagBytes + kSlotBytes) return false;
-    if (hipMemset(p, 0, kFlagBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-        (void)hipGetLastError();
-        return false;
-    }
+static Scratch carve(void* p, size_t bytes) {
+    Scratch sc;
     sc.flags = static_cast<uint32_t*>(p);
     sc.partials = reinterpret_cast<float*>(static_cast<char*>(p) + kFlagBytes);
     sc.partial_bytes = bytes - kFlagBytes;
-    return true;
+    return sc;
 }
 
-// The current device's scratch area (by value: a later set_workspace does not disturb a launch being
-// prepared), with room for `bytes_needed` bytes of partial tiles; .partials == nullptr if that cannot be had.
-static Scratch get_scratch(size_t bytes_needed) {
+// The current device's registered area (by value: a later set_workspace does not disturb a launch
+// being prepared) if it has room for `bytes_needed` bytes of partial tiles; else .partials == nullptr.
+static Scratch registered_scratch(size_t bytes_needed) {
     int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Scratch{};
-    std::lock_guard<std::mutex> lock(g_scratch_mutex);
-    Scratch& sc = g_scratch[dev];
-    if (!sc.partials) {
-        void* p = nullptr;
-        const size_t bytes = kFlagBytes + kScratchSlots * kSlotBytes;
-        if (hipMalloc(&p, bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return Scratch{};
-        }
-        if (!adopt(sc, p, bytes)) {
-            (void)hipFree(p);
-            return Scratch{};
-        }
-        sc.owned = p;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return Scratch{};
     }
-    return sc.partial_bytes >= bytes_needed ? sc : Scratch{};
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    const Scratch& sc = g_scratch[dev];
+    return (sc.partials && sc.partial_bytes >= bytes_needed) ? sc : Scratch{};
 }
 
 static std::atomic<int> g_forced{-1};
@@ -544,11 +487,14 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     if (forced >= 0) {
         if (!variant_supports(forced, M, N, K, layout)) return AXONN_ERR_UNSUPPORTED;
         plan = Plan{1, {{forced, M, N, 0, 0}}};
-        if (split_bytes(plan) && !(scratch = get_scratch(split_bytes(plan))).partials) return AXONN_ERR_WORKSPACE;
     } else {
         plan = cached_plan(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
-        if (split_bytes(plan) && !(scratch = get_scratch(split_bytes(plan))).partials)
-            plan = cached_plan(M, N, K, layout, false);
+    }
+    if (const size_t need = split_bytes(plan)) {
+        if (!(scratch = registered_scratch(need)).partials) {
+            if (forced >= 0) return AXONN_ERR_WORKSPACE;
+            plan = cached_plan(M, N, K, layout, false);   // no area, or too small a one: the kernels that need none
+        }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint16_t* A = static_cast<const uint16_t*>(a);
@@ -557,8 +503,8 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
 
     (void)hipGetLastError();
     if (g_variants[plan.part[0].variant].bm == 0) {
-        const dim3 grid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16));
-        if (grid.y > 65535u * 16u) return AXONN_ERR_UNSUPPORTED;
+        const int64_t blocks = ((M + 15) / 16) * ((N + 15) / 16);
+        const dim3 grid((unsigned)std::min<int64_t>(blocks, (int64_t)1 << 20));
         switch (layout) {
             case AXONN_NN: hipLaunchKernelGGL(gemm_naive_kernel<AXONN_NN>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
             case AXONN_NT: hipLaunchKernelGGL(gemm_naive_kernel<AXONN_NT>, grid, dim3(256), 0, s, A, B, C, M, N, K); break;
@@ -701,7 +647,7 @@ const char* axonn_status_string(int status) {
         case AXONN_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad dimension, layout or flag)";
         case AXONN_ERR_UNSUPPORTED: return "the forced kernel variant cannot run this shape";
         case AXONN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-        case AXONN_ERR_WORKSPACE: return "no split-K scratch area (allocation failed or the registered workspace is too small)";
+        case AXONN_ERR_WORKSPACE: return "no split-K scratch area of the size needed (none registered, or the registered one too small)";
         default: return "unknown status";
     }
 }
@@ -731,15 +677,26 @@ int axonn_linear_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_pa
     return plan.parts;
 }
 
+int axonn_linear_call_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_plan_part_t parts[AXONN_MAX_PLAN_PARTS]) {
+    if (M <= 0 || N <= 0 || K < 0 || layout < 0 || layout > 2 || !parts) return AXONN_ERR_INVALID_ARG;
+    axonn::Plan plan = axonn::cached_plan(M, N, K, layout, axonn::g_split_k_enabled.load(std::memory_order_relaxed) != 0);
+    if (const size_t need = axonn::split_bytes(plan))
+        if (!axonn::registered_scratch(need).partials) plan = axonn::cached_plan(M, N, K, layout, false);
+    for (int i = 0; i < plan.parts; ++i)
+        parts[i] = axonn_plan_part_t{plan.part[i].variant, plan.part[i].m, plan.part[i].n, plan.part[i].row0, plan.part[i].col0};
+    return plan.parts;
+}
+
 int axonn_linear_init(void) {
     axonn::raise_lds_limits_once();
-    return axonn::get_scratch(axonn::kSlotBytes).partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
+    return AXONN_OK;
 }
 
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout) {
     if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return 0;
     const size_t bytes = axonn::split_bytes(axonn::cached_plan(M, N, K, layout, true));
-    return bytes ? axonn::kFlagBytes + bytes : 0;
+    // never less than what axonn_linear_set_workspace accepts (a plan of 128 x 128 tiles can need less)
+    return bytes ? axonn::kFlagBytes + std::max(bytes, axonn::kSlotBytes) : 0;
 }
 
 int axonn_linear_set_workspace(void* dev_ptr, size_t bytes) {
@@ -748,14 +705,17 @@ int axonn_linear_set_workspace(void* dev_ptr, size_t bytes) {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= axonn::kMaxDevices) return AXONN_ERR_LAUNCH;
     std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
     axonn::Scratch& sc = axonn::g_scratch[dev];
-    if (dev_ptr == nullptr) {            // back to a library-owned area (made on next need)
-        if (!sc.owned) sc = axonn::Scratch{};
+    if (dev_ptr == nullptr) {            // unregistered: from now on the kernels that need no scratch
+        sc = axonn::Scratch{};
         return AXONN_OK;
     }
-    axonn::Scratch fresh;
-    if (!axonn::adopt(fresh, dev_ptr, bytes)) return AXONN_ERR_WORKSPACE;
-    if (sc.owned) (void)hipFree(sc.owned);   // no launch may be in flight (documented)
-    sc = fresh;
+    if (bytes < axonn::kFlagBytes + axonn::kSlotBytes) return AXONN_ERR_WORKSPACE;
+    // flags start at zero (a flag is valid when it equals the launch's non-zero epoch)
+    if (hipMemset(dev_ptr, 0, axonn::kFlagBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        return AXONN_ERR_WORKSPACE;
+    }
+    sc = axonn::carve(dev_ptr, bytes);
     return AXONN_OK;
 }
 
@@ -774,7 +734,7 @@ int axonn_linear_split_k_timeouts(uint64_t* count) {
         std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
         if (axonn::g_scratch[dev].flags) counter = axonn::g_scratch[dev].timeouts();
     }
-    if (!counter) return AXONN_OK;   // no split-K kernel has run on this device
+    if (!counter) return AXONN_OK;   // no area registered on this device
     uint32_t v = 0;
     if (hipMemcpy(&v, counter, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
@@ -782,26 +742,6 @@ int axonn_linear_split_k_timeouts(uint64_t* count) {
     }
     *count = v;
     return AXONN_OK;
-}
-
-int axonn_linear_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
-    if (!src || !dst || (bytes & 15) || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
-        return AXONN_ERR_INVALID_ARG;
-    if (bytes == 0) return AXONN_OK;
-    (void)hipGetLastError();
-    hipLaunchKernelGGL(axonn::copy_probe_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const axonn::u32x4*>(src), static_cast<axonn::u32x4*>(dst), bytes / 16);
-    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
-}
-
-int axonn_linear_mfma_probe(const void* data, size_t data_bytes, int iters, int workgroups, void* sink, void* stream) {
-    if (!data || !sink || (reinterpret_cast<uintptr_t>(data) & 15) || data_bytes < 32u * 256u * 16u || iters < 0 ||
-        workgroups < 1 || workgroups > 65536)
-        return AXONN_ERR_INVALID_ARG;
-    (void)hipGetLastError();
-    hipLaunchKernelGGL(axonn::mfma_probe_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const axonn::u32x4*>(data), static_cast<float*>(sink), iters);
-    return hipGetLastError() == hipSuccess ? AXONN_OK : AXONN_ERR_LAUNCH;
 }
 
 int axonn_transpose_bf16(int64_t rows, int64_t cols, const void* src, void* dst, void* stream) {

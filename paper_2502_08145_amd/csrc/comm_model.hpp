@@ -1,4 +1,4 @@
-// Communication performance model of the 4D-parallel method (paper Sec. V-A, Eq. 1-7): host-only
+// Communication performance model of the 4D-parallel method (paper Sec. IV-B, Eq. 1-7): host-only
 // arithmetic that ranks the grids G_x x G_y x G_z x G_data a job of G GPUs could use by the time
 // their collectives take.  It tells a multi-GPU deployment which shard shapes the GEMM kernels of
 // this library will be asked for.  No GPU is touched.

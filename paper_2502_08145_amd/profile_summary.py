@@ -6,8 +6,10 @@ counter means) and, on request, into the HBM bytes per launch that bench.py repo
 
 Each <dir> is the -d directory of one rocprofv3 run (--kernel-trace, with --stats and/or --pmc).
 --traffic prints a JSON object {workload: {kernel: bytes per launch}}: FETCH_SIZE and WRITE_SIZE
-(KiB per dispatch) of every GEMM kernel, each scaled by what the same counter read for the copy
-probe of <copy MiB> MiB that ran in the same process (bench.py --calibrate-copy).
+(KiB per dispatch) of every GEMM kernel, each scaled by what the same counter read for a kernel of
+exactly known traffic that ran in the same process: the tiled transpose of a <copy MiB> MiB matrix
+(bench.py --calibrate-copy; every element read once and written once).  The object also carries
+the hash of the kernel sources it was measured with ("_source", build.source_id()).
 """
 from __future__ import annotations
 
@@ -31,8 +33,8 @@ def short(name: str) -> str:
         wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
         return f"mfma16k64_256x256{'_w8' if wn == '4' else ''}{'_sk' if split == 'true' else ''}/{lay}"
-    if "copy_probe_kernel" in name:
-        return "copy_probe"
+    if "transpose_tile_kernel" in name:
+        return "transpose_tile"
     if "gemm_naive_kernel" in name:
         return "naive"
     return re.sub(r"\(.*", "", name)[:60]
@@ -50,7 +52,7 @@ def summarize(d: str, out=sys.stdout):
         for r in csv.DictReader(open(f)):
             ctr[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
     print(f"== {d}", file=out)
-    keys = [k for k in dur if k.startswith(("mfma", "copy_probe", "naive"))]
+    keys = [k for k in dur if k.startswith(("mfma", "transpose_tile", "naive"))]
     for k in sorted(keys, key=lambda k: -sum(dur[k])):
         v = dur[k]
         print(f"{k:<22s} calls {len(v):5d}  mean {sum(v) / len(v) / 1e3:9.2f} us  min {min(v) / 1e3:9.2f}  "
@@ -72,14 +74,17 @@ def traffic(workload: str, copy_mib: float, fetch_dir: str, write_dir: str) -> d
     _, write = summarize(write_dir, io.StringIO())
     mean = lambda v: sum(v) / len(v)
     kib = copy_mib * 1024.0
-    f_scale = kib / mean(fetch["copy_probe"]["FETCH_SIZE"])
-    w_scale = kib / mean(write["copy_probe"]["WRITE_SIZE"])
+    f_scale = kib / mean(fetch["transpose_tile"]["FETCH_SIZE"])
+    w_scale = kib / mean(write["transpose_tile"]["WRITE_SIZE"])
     out = {}
     for k in fetch:
         if k.startswith("mfma") and k in write:
             out[k] = int(round(1024.0 * (mean(fetch[k]["FETCH_SIZE"]) * f_scale + mean(write[k]["WRITE_SIZE"]) * w_scale)))
+    from .build import source_id
     return {workload: out, "_scale": {"FETCH_SIZE": round(f_scale, 4), "WRITE_SIZE": round(w_scale, 4)},
-            "_note": "bytes per launch = FETCH_SIZE x scale + WRITE_SIZE x scale (KiB -> bytes), scales from the copy probe"}
+            "_source": source_id(),
+            "_note": "bytes per launch = FETCH_SIZE x scale + WRITE_SIZE x scale (KiB -> bytes), scales from a tiled "
+                     "transpose of known size in the same process; _source = hash of the kernel sources measured"}
 
 
 def main(argv):

@@ -2,20 +2,14 @@
 
     python -m paper_2502_08145_amd.sweeps peak_curve [--max 65536]
     python -m paper_2502_08145_amd.sweeps model_zoo [--tokens 2048]
-    python -m paper_2502_08145_amd.sweeps power_clock [--vendor]
 
 peak_curve   square bf16 GEMMs 1024 ... 65536 in the three modes, the protocol of the paper's
              single-GPU GEMM benchmark (Sec. V-C: repeated runs, mean of the last three quarters),
              with the repetition count scaled down so that one size takes a few seconds.
-model_zoo    the shard shapes of the paper's model table (Sec. V-A, Table II: hidden 4096 ... 16384,
+model_zoo    the shard shapes of the paper's model table (Sec. V-A, the table of GPT models: hidden 4096 ... 16384,
              FFN 4h, fused QKV 3h) under every split of a weight's two dimensions by 1, 2, 4 or 8
              (Sec. IV-A: a weight is sharded over two of the grid's dimensions), forward,
              backward-data and backward-weight in their natural modes.
-
-power_clock  shader clock of every XCD and socket power, read from amd-smi while one GEMM is
-             launched back to back for a few seconds: shows whether the path runs into the board's
-             power limit, which lowers the clock below the 2.4 GHz the published MFMA peak assumes.
-             --vendor adds torch.matmul (the vendor BLAS) on the same operands, as context.
 
 Operands are N(0,1) (activations, gradients) and N(0, 0.02^2) (weights) drawn on the device with a
 fixed seed: host generation of 65536^2 matrices would take minutes.  Output: one text line per
@@ -122,97 +116,6 @@ def smi_sample():
     return parse_smi(subprocess.run(["amd-smi", "metric", "-c", "-p"], capture_output=True, text=True, timeout=30).stdout)
 
 
-def power_clock(args):
-    gen = torch.Generator(device="cuda").manual_seed(250208147)
-    stream = torch.cuda.current_stream()
-    cases = [("bwd_weight", 4096, 16384, 2048, "TN"), ("fwd", 2048, 16384, 4096, "NN"),
-             ("bwd_data", 2048, 4096, 16384, "NT"), ("fwd", 8192, 8192, 8192, "NT")]
-    print(f"{'M':>6s} {'N':>6s} {'K':>6s} {'mode':>4s} {'kernel':<28s} {'TFLOP/s':>8s} {'W':>5s} {'MHz mean':>8s} "
-          f"{'min':>5s} {'max':>5s} {'% of peak at that clock':>24s}")
-    for op, M, N, K, layout in cases:
-        ashape = (K, M) if layout == "TN" else (M, K)
-        bshape = (N, K) if layout == "NT" else (K, N)
-        a = [randn_bf16(ashape, 1.0, gen) for _ in range(4)]
-        b = [randn_bf16(bshape, 1.0, gen) for _ in range(4)]
-        c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-
-        def ours(i):
-            B.OPS[op](M, N, K, layout, a[i % 4], b[i % 4], c, 1, stream)
-
-        def vendor(i):
-            x = a[i % 4].t() if layout == "TN" else a[i % 4]
-            y = b[i % 4].t() if layout == "NT" else b[i % 4]
-            torch.matmul(x, y, out=c)
-
-        runs = [(B.plan_name(M, N, K, layout), ours)] + ([("torch.matmul (vendor BLAS)", vendor)] if args.vendor else [])
-        for name, launch in runs:
-            for i in range(8):
-                launch(i)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for i in range(8):
-                launch(i)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            for i in range(int(1000.0 * 8 / max(e0.elapsed_time(e1), 1e-3))):   # a second of work: clocks and power settle
-                launch(i)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for i in range(50):
-                launch(i)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 50
-            watts, mhz = [], []
-            for _ in range(3):
-                for i in range(int(1500.0 / ms)):          # about 1.5 s of queued work, sampled while it runs
-                    launch(i)
-                w, clk = smi_sample()
-                torch.cuda.synchronize()
-                if w is not None and clk:
-                    watts.append(w)
-                    mhz += clk
-            if not mhz:
-                sys.exit("power_clock: amd-smi gave no clock or power reading")
-            tf = 2.0 * M * N * K / ms / 1e9
-            mean = sum(mhz) / len(mhz)
-            at_clock = PEAK * mean / 2400.0
-            print(f"{M:6d} {N:6d} {K:6d} {layout:>4s} {name:<28s} {tf:8.1f} {sum(watts) / len(watts):5.0f} {mean:8.0f} "
-                  f"{min(mhz):5d} {max(mhz):5d} {tf / at_clock * 100:23.1f}%", flush=True)
-        del a, b, c
-    # the matrix pipes alone, on N(0,1) operand values held in registers: what the board's power limit
-    # leaves of the clock when nothing but MFMAs run
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    data = randn_bf16((1 << 20,), 1.0, gen)
-    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    iters = 4000
-    for _ in range(200):     # about a second: clocks and power settle
-        B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(20):
-        B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / 20
-    watts, mhz = [], []
-    for _ in range(3):
-        for _ in range(int(1500.0 / ms)):
-            B.axonn_linear_mfma_probe(data, iters, cus, sink, stream)
-        w, clk = smi_sample()
-        torch.cuda.synchronize()
-        if w is not None and clk:
-            watts.append(w)
-            mhz += clk
-    tf = cus * 4 * iters * 64 * 32768.0 / (ms * 1e-3) / 1e12
-    mean = sum(mhz) / len(mhz)
-    print(f"{'':>6s} {'':>6s} {'':>6s} {'':>4s} {'MFMA-only probe, N(0,1)':<28s} {tf:8.1f} {sum(watts) / len(watts):5.0f} {mean:8.0f} "
-          f"{min(mhz):5d} {max(mhz):5d} {tf / (PEAK * mean / 2400.0) * 100:23.1f}%", flush=True)
-
-
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -221,15 +124,13 @@ def main(argv=None):
     z = sub.add_parser("model_zoo")
     z.add_argument("--tokens", type=int, default=2048)
     z.add_argument("--verbose", action="store_true")
-    w = sub.add_parser("power_clock")
-    w.add_argument("--vendor", action="store_true")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("sweeps: no GPU visible")
     B.lib()
-    B.axonn_linear_init()
     torch.cuda.set_device(0)
-    {"peak_curve": peak_curve, "model_zoo": model_zoo, "power_clock": power_clock}[args.cmd](args)
+    B.register_workspace()          # the library allocates nothing: split-K scratch is ours to provide
+    {"peak_curve": peak_curve, "model_zoo": model_zoo}[args.cmd](args)
 
 
 if __name__ == "__main__":

@@ -59,6 +59,28 @@ def _normal_chunk(seed: int, start: int, cnt: int, sigma: float) -> np.ndarray:
     return f32_to_bf16_bits(v)
 
 
+def _workers(workers):
+    if workers is None:
+        try:
+            workers = len(os.sched_getaffinity(0))
+        except AttributeError:  # pragma: no cover
+            workers = os.cpu_count() or 1
+        workers = max(1, min(16, workers))
+    return workers
+
+
+def _in_chunks(total: int, chunk: int, workers, work) -> None:
+    """work(start, count) over [0, total) in pieces of `chunk`, on a thread pool."""
+    starts = list(range(0, total, chunk))
+    workers = _workers(workers)
+    if workers == 1 or len(starts) <= 1:
+        for st in starts:
+            work(st, min(chunk, total - st))
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(lambda st: work(st, min(chunk, total - st)), starts))
+
+
 def normal_bf16(seed: int, shape, sigma: float = 1.0, chunk: int = 1 << 20, workers: int | None = None) -> np.ndarray:
     """N(0, sigma^2) samples as bf16 bits, shape `shape`, row-major element numbering.
 
@@ -67,37 +89,32 @@ def normal_bf16(seed: int, shape, sigma: float = 1.0, chunk: int = 1 << 20, work
     shape = tuple(int(s) for s in shape)
     total = int(np.prod(shape)) if shape else 1
     out = np.empty(total, dtype=np.uint16)
-    starts = list(range(0, total, chunk))
-    if workers is None:
-        try:
-            workers = len(os.sched_getaffinity(0))
-        except AttributeError:  # pragma: no cover
-            workers = os.cpu_count() or 1
-        workers = max(1, min(16, workers))
 
-    def work(start):
-        cnt = min(chunk, total - start)
+    def work(start, cnt):
         out[start:start + cnt] = _normal_chunk(seed, start, cnt, sigma)
 
-    if workers == 1 or len(starts) <= 1:
-        for st in starts:
-            work(st)
-    else:
-        with ThreadPoolExecutor(max_workers=workers) as ex:
-            list(ex.map(work, starts))
+    _in_chunks(total, chunk, workers, work)
     return out.reshape(shape)
 
 
-def integer_bf16(seed: int, shape, lo: int = -4, hi: int = 4) -> np.ndarray:
-    """Uniform integers in [lo, hi] (inclusive) as bf16 bits; |values| <= 256 are exact in bf16."""
+def integer_bf16(seed: int, shape, lo: int = -4, hi: int = 4, chunk: int = 1 << 20, workers: int | None = None) -> np.ndarray:
+    """Uniform integers in [lo, hi] (inclusive) as bf16 bits; |values| <= 256 are exact in bf16.
+
+    The result does not depend on `chunk` or `workers` (element n is a function of (seed, n))."""
     if max(abs(lo), abs(hi)) > 256:
         raise ValueError("integers beyond 256 are not all exact in bf16")
     shape = tuple(int(s) for s in shape)
     total = int(np.prod(shape)) if shape else 1
-    h = _hash_stream(seed, total)
+    out = np.empty(total, dtype=np.uint16)
     span = np.uint64(hi - lo + 1)
-    v = ((h >> np.uint64(11)) % span).astype(np.int64) + lo
-    return f32_to_bf16_bits(v.astype(np.float32)).reshape(shape)
+
+    def work(start, cnt):
+        h = _hash_stream(seed, cnt, start)
+        v = ((h >> np.uint64(11)) % span).astype(np.int64) + lo
+        out[start:start + cnt] = f32_to_bf16_bits(v.astype(np.float32))
+
+    _in_chunks(total, chunk, workers, work)
+    return out.reshape(shape)
 
 
 def transpose_bits(a: np.ndarray) -> np.ndarray:

@@ -6,6 +6,21 @@ NORMWISE_TOL = 1e-2      # ||C_gpu - C_ref||_F / ||C_ref||_F
 ELEMENTWISE_TOL = 2e-2   # max |C_gpu - C_ref| / max |C_ref|
 
 
+_shared_ws = None
+
+
+def shared_workspace():
+    """Register (again) the one torch-owned split-K scratch area the GPU tests share: 4 KiB of flags
+    plus 256 slots of a 256 x 256 fp32 tile, which covers every product."""
+    global _shared_ws
+    from paper_2502_08145_amd import binding as B
+    torch.cuda.synchronize()
+    if _shared_ws is None:
+        _shared_ws = torch.empty((B.WORKSPACE_ALL,), dtype=torch.uint8, device="cuda")
+    B.axonn_linear_set_workspace(_shared_ws)
+    return _shared_ws
+
+
 def to_device(bits: np.ndarray) -> torch.Tensor:
     """numpy uint16 bf16 bit patterns -> bf16 CUDA tensor holding exactly those bits."""
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)

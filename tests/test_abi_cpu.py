@@ -126,6 +126,12 @@ def test_workspace_queries_are_host_only():
     assert B.axonn_linear_workspace_bytes(8192, 8192, 8192, "TN") == 0
     assert B.axonn_linear_workspace_bytes(100, 200, 300, "NN") == 0
     assert B.axonn_linear_workspace_bytes(0, 8, 8, "NN") == 0
+    # a plan of 128 x 128 tiles with few slots: never less than what set_workspace accepts
+    assert "128x128_sk" in B.plan_name(128, 128, 8192, "NT")
+    assert B.axonn_linear_workspace_bytes(128, 128, 8192, "NT") == 4096 + 256 * 256 * 4
+    # without a GPU no area can be registered: a call made now would run without split-K
+    assert "_sk" in B.plan_name(2048, 4096, 16384, "NT") and "_sk" not in B.plan_name(2048, 4096, 16384, "NT", now=True)
+    assert B.plan_name(8192, 8192, 8192, "TN", now=True) == B.plan_name(8192, 8192, 8192, "TN")
     L = B.lib()
     assert L.axonn_linear_set_workspace(0x1000, 0) == B.AXONN_ERR_INVALID_ARG      # pointer without size
     assert L.axonn_linear_set_workspace(None, 4096) == B.AXONN_ERR_INVALID_ARG     # size without pointer

@@ -1,4 +1,4 @@
-"""Pins for the oracle of the communication model (Sec. V-A, Eq. 1-7): hand-worked values, the
+"""Pins for the oracle of the communication model (Sec. IV-B, Eq. 1-7): hand-worked values, the
 two bandwidth examples the paper walks through, closed forms and counting arguments."""
 import math
 

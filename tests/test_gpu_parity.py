@@ -93,6 +93,14 @@ def _announce(request):
     yield
 
 
+@pytest.fixture(autouse=True)
+def _workspace():
+    """The library allocates nothing: every test runs with a torch-owned split-K scratch area of the
+    largest size any product needs, registered afresh (tests that register their own restore this)."""
+    U.shared_workspace()
+    yield
+
+
 # ------------------------------------------------------------------ ragged shapes, guarded kernel
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 1, 33), (1, 64, 1), (37, 53, 71), (130, 257, 65)])
@@ -288,16 +296,21 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
 
 
 def test_caller_owned_workspace(oracle_mod):
-    # the same split-K problem through the library's own scratch area, through a registered buffer
-    # that is large enough, and with one that is too small (automatic choice then avoids split-K,
-    # a forced split-K variant is refused)
+    # the same split-K problem through a registered buffer that is large enough, with one that is too
+    # small (automatic choice then avoids split-K, a forced split-K variant is refused) and with none
     M, N, K, layout = 512, 1024, 1792, "NT"
     a = synth.integer_bf16(93, (M, K), -4, 4)
     b = synth.integer_bf16(94, (K, N), -4, 4)
     A, Bm = store(a, b, layout)
     want = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M, N, K, layout, A, Bm))
-    sk2 = next(v for v in tile_variants() if B.variant_name(v) == "mfma_256x256_w8_sk2")
+    sk2 = next(v for v in tile_variants() if B.variant_name(v) == "mfma16_256x256_w8_sk2")
     need = 4096 + 8 * 256 * 256 * 4
+    M2, N2, K2 = 1024, 1024, 4096        # a split-K-worthy shape for the automatic choice
+    a2 = synth.integer_bf16(95, (M2, K2), -4, 4)
+    b2 = synth.integer_bf16(96, (K2, N2), -4, 4)
+    A2, B2 = store(a2, b2, layout)
+    want2 = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M2, N2, K2, layout, A2, B2))
+    assert "_sk" in B.plan_name(M2, N2, K2, layout)
     try:
         big = torch.full((need + 4096,), 0x55, dtype=torch.uint8, device="cuda")     # dirty on purpose
         B.axonn_linear_set_workspace(big)
@@ -308,7 +321,7 @@ def test_caller_owned_workspace(oracle_mod):
         flags = big[:4096].view(torch.int32).cpu().numpy()
         assert not flags[:1023].any() and flags[1023] == 0, "split-K flags left standing, or a time-out"
         # ... also by the other kernel families
-        for name in ("mfma16_256x256_w8_sk2", "mfma16k64_256x256_w8_sk2", "mfma16_128x128_sk2"):
+        for name in ("mfma16k64_256x256_w8_sk2", "mfma16_128x128_sk2"):
             v16 = [B.variant_name(v) for v in range(B.num_variants())].index(name)
             assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=v16), want), name
             assert not big[:4096].view(torch.int32).cpu().numpy().any(), name
@@ -321,16 +334,37 @@ def test_caller_owned_workspace(oracle_mod):
             assert rc == B.AXONN_ERR_WORKSPACE
         finally:
             B.force_variant(-1)
-        # automatic selection for a split-K-worthy shape still gives the right answer
-        M2, N2, K2 = 1024, 1024, 4096
-        a2 = synth.integer_bf16(95, (M2, K2), -4, 4)
-        b2 = synth.integer_bf16(96, (K2, N2), -4, 4)
-        A2, B2 = store(a2, b2, layout)
+        # automatic selection for a split-K-worthy shape still gives the right answer, without split-K
         assert B.axonn_linear_workspace_bytes(M2, N2, K2, layout) > small.numel()
-        want2 = U.f64_to_bf16_bits_rne(oracle_mod.gemm(M2, N2, K2, layout, A2, B2))
+        assert "_sk" not in B.plan_name(M2, N2, K2, layout, now=True)
+        assert np.array_equal(run_gpu("fwd", M2, N2, K2, layout, A2, B2), want2)
+        # no area registered at all: the library allocates none of its own
+        torch.cuda.synchronize()
+        B.axonn_linear_set_workspace(None)
+        big.fill_(0x55)
+        torch.cuda.synchronize()
+        assert "_sk" not in B.plan_name(M2, N2, K2, layout, now=True)
+        assert np.array_equal(run_gpu("fwd", M2, N2, K2, layout, A2, B2), want2)
+        B.force_variant(sk2)
+        try:
+            c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            rc = B.axonn_linear_fwd(M, N, K, layout, U.to_device(A), U.to_device(Bm), c, check=False)
+            assert rc == B.AXONN_ERR_WORKSPACE
+        finally:
+            B.force_variant(-1)
+        assert B.axonn_linear_split_k_timeouts() == 0
+        assert (big == 0x55).all(), "an unregistered buffer was written"
+        # exactly the advertised size is accepted, for a plan of small tiles too
+        for shape in ((M2, N2, K2), (128, 128, 8192)):
+            nb = B.axonn_linear_workspace_bytes(*shape, layout)
+            assert nb >= 4096 + 256 * 256 * 4
+            exact = torch.zeros((nb,), dtype=torch.uint8, device="cuda")
+            B.axonn_linear_set_workspace(exact)
+            assert B.plan_name(*shape, layout, now=True) == B.plan_name(*shape, layout)
         assert np.array_equal(run_gpu("fwd", M2, N2, K2, layout, A2, B2), want2)
     finally:
-        B.axonn_linear_set_workspace(None)
+        U.shared_workspace()
+    assert "_sk" in B.plan_name(M2, N2, K2, layout, now=True)
     assert np.array_equal(run_gpu("fwd", M, N, K, layout, A, Bm, variant=sk2), want)
     assert B.axonn_linear_split_k_timeouts() == 0
 
@@ -419,7 +453,6 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(variant, shape):
     names = [B.variant_name(v) for v in range(B.num_variants())]
     v = names.index(variant) if variant else -1
     assert v < 0 or B.variant_supports(v, M, N, K, "NT")
-    B.axonn_linear_init()
     gen = torch.Generator(device="cuda").manual_seed(77)
     a = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
     b = torch.randn((N, K), generator=gen, device="cuda").to(torch.bfloat16)
@@ -475,34 +508,73 @@ def _sample_positions(M, N, seed, n_rows=4, n_cols=4, block=128):
 
 
 FULL_SIZE = [
-    # (name, tokens, d_in, d_out): layers whose three GEMMs are the benchmark shapes
+    # (name, tokens, d_in, d_out): every layer of the benchmark workloads above the tiny one
     ("gpt5b.qkv", 2048, 4096, 12288),
+    ("gpt5b.attn_out", 2048, 4096, 4096),
+    ("gpt5b.fc1", 2048, 4096, 16384),
     ("gpt5b.fc2", 2048, 16384, 4096),
     ("gpt80b_shard.fc1", 4096, 2048, 16384),
+    ("gpt80b_shard.fc2", 4096, 16384, 2048),
     ("gpt320b_skinny.fc1", 2048, 2048, 8192),
+    ("gpt320b_skinny.fc2", 2048, 8192, 2048),
 ]
 
 
 @pytest.mark.parametrize("name,tokens,d_in,d_out", FULL_SIZE)
-def test_full_size_layers_sampled(oracle_mod, name, tokens, d_in, d_out):
-    """Benchmark-size GEMMs in the launch configuration bench.py times (automatic variant),
-    checked on full rows, full columns and one seeded element per 128x128 block."""
+def test_full_size_layers_every_element(oracle_mod, name, tokens, d_in, d_out):
+    """Benchmark-size GEMMs in the launch configuration bench.py times (automatic plan, split-K
+    scratch registered): forward, backward-data and backward-weight of the layer, each in all three
+    modes, the WHOLE output against the whole oracle product."""
     t = synth.fc_layer_tensors(tokens, d_in, d_out, synth.BASE_SEED + 300)
     for g in synth.fc_layer_gemms(tokens, d_in, d_out, name):
         M, N, K = g["M"], g["N"], g["K"]
-        ii, jj = _sample_positions(M, N, seed=M + N)
-        ref = None
-        for layout in LAYOUTS:
+        A, Bm = synth.operands_for(g["op"], g["layout"], t)
+        print(f"  {g['name']} {M}x{N}x{K}: oracle ...", flush=True)
+        ref = oracle_mod.gemm(M, N, K, g["layout"], A, Bm)
+        for layout in LAYOUTS:   # all three modes of one GEMM have the same reference result
             A, Bm = synth.operands_for(g["op"], layout, t)
-            if ref is None:
-                ref = oracle_mod.gemm_at(M, N, K, layout, A, Bm, ii, jj)
+            assert B.plan_name(M, N, K, layout, now=True) == B.plan_name(M, N, K, layout)
             got = run_gpu(g["op"], M, N, K, layout, A, Bm)
-            assert np.isfinite(U.bits_to_f64(got)).all(), f"{g['name']} {layout}: non-finite output"
-            U.assert_close(got[ii, jj], ref, f"{g['name']} {layout}")
+            nw, ew = U.assert_close(got, ref, f"{g['name']} {layout}")
+            assert nw < 4e-3, (g["name"], layout, nw)   # the bf16 rounding floor is 2^-9 rms
+        del ref
 
 
-@pytest.mark.parametrize("n", [4096, 8192, 16384])
-def test_square_layout_sweep_sampled(oracle_mod, n):
+@pytest.mark.parametrize("name,tokens,d_in,d_out", FULL_SIZE)
+def test_full_size_layers_integer_data_bit_for_bit(oracle_mod, name, tokens, d_in, d_out):
+    """The same shapes on integer-valued operands in their natural modes (the launches bench.py times):
+    every partial sum is an integer below 2^24, exact in fp32 whatever the order, so sampled rows,
+    columns and one element per 128 x 128 block must equal the rounded oracle value bit for bit."""
+    t = dict(X=synth.integer_bf16(synth.BASE_SEED + 310, (tokens, d_in), -4, 4),
+             W=synth.integer_bf16(synth.BASE_SEED + 311, (d_in, d_out), -4, 4),
+             dY=synth.integer_bf16(synth.BASE_SEED + 312, (tokens, d_out), -4, 4))
+    for g in synth.fc_layer_gemms(tokens, d_in, d_out, name):
+        M, N, K = g["M"], g["N"], g["K"]
+        ii, jj = _sample_positions(M, N, seed=M + 3 * N)
+        A, Bm = synth.operands_for(g["op"], g["layout"], t)
+        want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, g["layout"], A, Bm, ii, jj))
+        got = run_gpu(g["op"], M, N, K, g["layout"], A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all(), f"{g['name']}: unwritten or non-finite output"
+        bad = np.nonzero(got[ii, jj] != want)[0]
+        assert bad.size == 0, f"{g['name']}: {len(bad)} mismatches, first at {(ii[bad[0]], jj[bad[0]])}"
+
+
+@pytest.mark.parametrize("n", [1024, 2048, 4096, 8192])
+def test_square_layout_sweep_every_element(oracle_mod, n):
+    """Square products of the layout sweep and of the empirical-peak curve (the paper's single-GPU GEMM
+    benchmark, Sec. V-C), whole output, all three modes."""
+    a = synth.normal_bf16(synth.BASE_SEED + 500, (n, n))
+    b = synth.normal_bf16(synth.BASE_SEED + 501, (n, n))
+    ref = oracle_mod.gemm(n, n, n, "NN", a, b)
+    for layout in LAYOUTS:
+        A, Bm = store(a, b, layout)
+        got = run_gpu("fwd", n, n, n, layout, A, Bm)
+        nw, ew = U.assert_close(got, ref, f"square {n} {layout}")
+        assert nw < 4e-3, (n, layout, nw)
+
+
+def test_square_16384_sampled(oracle_mod):
+    n = 16384
     a = synth.normal_bf16(synth.BASE_SEED + 500, (n, n))
     b = synth.normal_bf16(synth.BASE_SEED + 501, (n, n))
     ii, jj = _sample_positions(n, n, seed=n, n_rows=2, n_cols=2)
@@ -512,6 +584,121 @@ def test_square_layout_sweep_sampled(oracle_mod, n):
         got = run_gpu("fwd", n, n, n, layout, A, Bm)
         assert np.isfinite(U.bits_to_f64(got)).all()
         U.assert_close(got[ii, jj], ref, f"square {n} {layout}")
+
+
+def _periodic_rows(seed, rows, cols, period, sigma=1.0):
+    """[rows, cols] whose rows repeat a seeded block of `period` rows (fast to make at sizes where
+    drawing every element on the host would take minutes)."""
+    block = synth.normal_bf16(seed, (period, cols), sigma)
+    reps = -(-rows // period)
+    return np.ascontiguousarray(np.tile(block, (reps, 1))[:rows])
+
+
+@pytest.mark.parametrize("n", [32768, 65536])
+def test_largest_squares_of_the_peak_curve_sampled(oracle_mod, n):
+    """The top of the empirical-peak curve (Sec. V-C): operands of 2 and 8.6 GB, where per-lane 32-bit
+    address offsets would wrap (at n = 65536 every MN-contiguous panel is above 4 GiB).  Both operands
+    repeat a seeded block of 5000 rows; 5000 divides neither 32768 rows (where a 4 GiB byte offset
+    wraps at n = 65536) nor any power of two, so an address that wraps lands on other data.  Outputs
+    are compared on sampled rows, columns and one element per 1024 x 1024 block, all three modes; the
+    other modes' operands are transposed on the device by torch (plumbing: bits moved)."""
+    a = _periodic_rows(synth.BASE_SEED + 510, n, n, 5000)
+    b = _periodic_rows(synth.BASE_SEED + 511, n, n, 5000)
+    ii, jj = _sample_positions(n, n, seed=n, n_rows=2, n_cols=2, block=1024)
+    print(f"  oracle at {len(ii)} positions ...", flush=True)
+    ref = oracle_mod.gemm_at(n, n, n, "NN", a, b, ii, jj)
+    a_d, b_d = U.to_device(a), U.to_device(b)
+    del a, b
+    c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+    ti, tj = torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()
+    for layout in LAYOUTS:
+        print(f"  {layout} ...", flush=True)
+        x = a_d.t().contiguous() if layout == "TN" else a_d
+        y = b_d.t().contiguous() if layout == "NT" else b_d
+        assert "edge" not in B.plan_name(n, n, n, layout, now=True) and B.plan_name(n, n, n, layout, now=True) != "naive"
+        c.view(torch.int16).fill_(0x7FC0)
+        B.axonn_linear_fwd(n, n, n, layout, x, y, c)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(c.view(-1)[:: 4099].float()).all()), "unwritten or non-finite output"
+        got = U.to_host_bits(c[ti, tj])
+        U.assert_close(got, ref, f"square {n} {layout}")
+        del x, y
+
+
+# ------------------------------------------------------------------ shard shapes of the paper's model table
+def _zoo_cases():
+    """A seeded subset of the shard shapes of the paper's GPT models (Sec. V-A, model table: hidden 5120,
+    7168, 9216, 12288 are the ones that are not powers of two; QKV 3h, FFN 4h) with both weight
+    dimensions split by 1, 2, 4 or 8 (Sec. IV-A): per hidden size three (layer, split) choices whose
+    weight shard stays below 2^25 elements, 2048 tokens."""
+    rng = np.random.default_rng(2502)
+    cases = []
+    for h in (5120, 7168, 9216, 12288):
+        layers = [("qkv", h, 3 * h), ("attn_out", h, h), ("fc1", h, 4 * h), ("fc2", 4 * h, h)]
+        pool = [(nm, di // ga, do // gb) for nm, di, do in layers for ga in (1, 2, 4, 8) for gb in (1, 2, 4, 8)
+                if (di // ga) * (do // gb) <= (1 << 25)]
+        for k in rng.choice(len(pool), size=3, replace=False):
+            cases.append((h,) + pool[int(k)])
+    return cases
+
+
+@pytest.mark.parametrize("h,layer,d_in,d_out", _zoo_cases())
+def test_model_zoo_shard_shapes_sampled(oracle_mod, h, layer, d_in, d_out):
+    """Forward, backward-data and backward-weight of a shard in their natural modes, automatic plan
+    (what the model-zoo sweep times), on sampled rows, columns and one element per 128 x 128 block."""
+    tokens = 2048
+    t = synth.fc_layer_tensors(tokens, d_in, d_out, synth.BASE_SEED + 600 + h)
+    for g in synth.fc_layer_gemms(tokens, d_in, d_out, f"h{h}.{layer}"):
+        M, N, K = g["M"], g["N"], g["K"]
+        ii, jj = _sample_positions(M, N, seed=M + N + K)
+        A, Bm = synth.operands_for(g["op"], g["layout"], t)
+        ref = oracle_mod.gemm_at(M, N, K, g["layout"], A, Bm, ii, jj)
+        got = run_gpu(g["op"], M, N, K, g["layout"], A, Bm)
+        assert np.isfinite(U.bits_to_f64(got)).all(), f"{g['name']}: unwritten or non-finite output"
+        U.assert_close(got[ii, jj], ref, f"{g['name']} {g['layout']} {B.plan_name(M, N, K, g['layout'])}")
+
+
+def test_model_zoo_plans_with_odd_split_counts_and_two_launches(oracle_mod):
+    """Among the model-zoo shard shapes the planner picks split-K with 3, 5 and 6 K ranges (7 is never
+    chosen there; test_every_tile_variant_against_oracle covers it) and plans of two launches: one
+    product of each kind is found by scanning the plans (host logic) and checked on sampled outputs,
+    N(0,1) data and integer data."""
+    tokens = 2048
+    wanted = {"_sk3": None, "_sk5": None, "_sk6": None, "+": None}
+    for h in (5120, 7168, 9216, 12288, 4096, 16384):
+        for nm, di, do in (("qkv", h, 3 * h), ("attn_out", h, h), ("fc1", h, 4 * h), ("fc2", 4 * h, h)):
+            for ga in (1, 2, 4, 8):
+                for gb in (1, 2, 4, 8):
+                    d_in, d_out = di // ga, do // gb
+                    if d_in * d_out > (5 << 23):
+                        continue
+                    for g in synth.fc_layer_gemms(tokens, d_in, d_out, f"h{h}.{nm}/{ga}x{gb}"):
+                        name = B.plan_name(g["M"], g["N"], g["K"], g["layout"])
+                        for key in wanted:
+                            hit = key in name if key == "+" else name.endswith(key) and "+" not in name
+                            if wanted[key] is None and hit:
+                                wanted[key] = (g, d_in, d_out, name)
+    assert all(v is not None for v in wanted.values()), {k: v for k, v in wanted.items() if v is None}
+    for key, (g, d_in, d_out, name) in wanted.items():
+        M, N, K = g["M"], g["N"], g["K"]
+        print(f"  {key}: {g['name']} {g['layout']} {M}x{N}x{K} {name}", flush=True)
+        ii, jj = _sample_positions(M, N, seed=M + K)
+        for kind in ("normal", "integer"):
+            if kind == "normal":
+                t = synth.fc_layer_tensors(tokens, d_in, d_out, synth.BASE_SEED + 650)
+            else:
+                t = dict(X=synth.integer_bf16(synth.BASE_SEED + 660, (tokens, d_in), -4, 4),
+                         W=synth.integer_bf16(synth.BASE_SEED + 661, (d_in, d_out), -4, 4),
+                         dY=synth.integer_bf16(synth.BASE_SEED + 662, (tokens, d_out), -4, 4))
+            A, Bm = synth.operands_for(g["op"], g["layout"], t)
+            ref = oracle_mod.gemm_at(M, N, K, g["layout"], A, Bm, ii, jj)
+            got = run_gpu(g["op"], M, N, K, g["layout"], A, Bm)
+            assert np.isfinite(U.bits_to_f64(got)).all(), f"{name}: unwritten or non-finite output"
+            if kind == "normal":
+                U.assert_close(got[ii, jj], ref, f"{g['name']} {name}")
+            else:
+                assert np.array_equal(got[ii, jj], U.f64_to_bf16_bits_rne(ref)), f"{g['name']} {name}: integer data"
+    assert B.axonn_linear_split_k_timeouts() == 0
 
 
 # ------------------------------------------------------------------ products cut into two launches
