@@ -111,6 +111,28 @@ int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout,
                             const void *X, const void *dY, void *dW,
                             int fp32_accumulate, void *stream);
 
+/* For callers that cannot allocate device memory or register a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same product as the three entry
+ * points above (which are one function under three names: `first`, `second`, `out` are X, W, Y /
+ * dY, W, dX / X, dY, dW), with the split-K kernels exchanging their partial tiles through a scratch
+ * area INSIDE the library: a file-scope device array of axonn_linear_static_scratch_bytes() =
+ * 4 KiB + 32 MiB that every GPU the library runs on holds from load until the process ends.  The call
+ * allocates nothing, frees nothing, synchronises nothing and ignores any registered workspace.
+ * Arguments, layouts, results and error codes are those of axonn_linear_fwd; in addition
+ *   - a product whose plan needs more than 128 partial tiles of 256 x 256 fp32 (32 MiB; for example
+ *     M = N = 2048, K = 32768: four K ranges on 64 tiles = 192 partial tiles) is refused with
+ *     AXONN_ERR_WORKSPACE and nothing is launched (use the entry points above with a registered
+ *     workspace for those);
+ *   - every call on one GPU uses that GPU's one array: calls that may execute concurrently on one GPU
+ *     (different streams) race on it; calls on one stream are safe.  The flag words start at zero
+ *     (the array is zero-filled at load) and every kernel leaves them at zero; partial tiles are
+ *     always written before they are read, so what an earlier call left there does not matter. */
+int axonn_linear_gemm_static(int64_t M, int64_t N, int64_t K, int layout,
+                             const void *first, const void *second, void *out,
+                             int fp32_accumulate, void *stream);
+/* Size in bytes of that array (per GPU).  Host only. */
+size_t axonn_linear_static_scratch_bytes(void);
+
 /* Operand re-storage for another mode (Sec. IV-C: the three modes differ only in how each operand
  * lies in memory): dst[cols, rows] = transpose of src[rows, cols], bf16 (16-bit) elements, bit
  * patterns moved unchanged.  DEVICE pointers, row-major, tightly packed, 2-byte aligned, not
@@ -211,19 +233,20 @@ int axonn_linear_version(void);
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout);
 int axonn_linear_set_workspace(void *dev_ptr, size_t bytes);
 
-/* Optional set-up for the current device: raises the kernels' LDS limits now rather than inside the
- * first GEMM call (hipFuncSetAttribute; no device memory is allocated, nothing is launched).
- * Idempotent.  Returns AXONN_OK. */
+/* Optional set-up for the current device: raises the kernels' LDS limits and looks up the device
+ * address of the static scratch array now rather than inside the first call that needs them
+ * (hipFuncSetAttribute, hipGetSymbolAddress; no device memory is allocated, nothing is launched).
+ * Idempotent.  AXONN_OK, or AXONN_ERR_WORKSPACE if the address look-up failed. */
 int axonn_linear_init(void);
 
 /* Allow (1, the default) or forbid (0) the automatic choice of split-K kernels, process-wide.
  * Returns the previous setting, or AXONN_ERR_INVALID_ARG. */
 int axonn_linear_set_split_k(int enable);
 
-/* Diagnostics: how many times, in the scratch area now registered on the current device, a split-K
- * workgroup gave up waiting for a partial tile (it waits about a second; this cannot happen unless
- * another workgroup of the same launch died).  Synchronous device-to-host copy.  *count is 0 when
- * no area is registered. */
+/* Diagnostics: how many times, in the scratch area now registered on the current device and in its
+ * static array together, a split-K workgroup gave up waiting for a partial tile (it waits about a
+ * second; this cannot happen unless another workgroup of the same launch died).  Synchronous
+ * device-to-host copies.  *count is 0 when neither has been used. */
 int axonn_linear_split_k_timeouts(uint64_t *count);
 
 /* Kernel variants.  Variant 0 is the guarded one-thread-per-element kernel that accepts any

@@ -21,6 +21,7 @@ AXONN_OK, AXONN_ERR_INVALID_ARG, AXONN_ERR_UNSUPPORTED, AXONN_ERR_LAUNCH, AXONN_
 
 EXPORTS = (
     "axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight",
+    "axonn_linear_gemm_static", "axonn_linear_static_scratch_bytes",
     "axonn_status_string", "axonn_linear_version", "axonn_linear_num_variants",
     "axonn_linear_variant_name", "axonn_linear_variant_supports", "axonn_linear_select_variant",
     "axonn_linear_plan", "axonn_linear_call_plan",
@@ -82,7 +83,9 @@ def lib() -> ctypes.CDLL:
                 "(there is no fallback implementation)")
         L = ctypes.CDLL(LIB_PATH)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
-        for name in ("axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight"):
+        L.axonn_linear_static_scratch_bytes.argtypes = []
+        L.axonn_linear_static_scratch_bytes.restype = ctypes.c_size_t
+        for name in ("axonn_linear_fwd", "axonn_linear_bwd_data", "axonn_linear_bwd_weight", "axonn_linear_gemm_static"):
             fn = getattr(L, name)
             fn.argtypes = [i64, i64, i64, ci, vp, vp, vp, ci, vp]
             fn.restype = ci
@@ -301,6 +304,15 @@ def axonn_linear_bwd_data(M, N, K, layout, dY, W, dX, fp32_accumulate=1, stream=
 def axonn_linear_bwd_weight(M, N, K, layout, X, dY, dW, fp32_accumulate=1, stream=None, check=True):
     """dW[M,N] = X^T * dY (Algorithm 1 line 13)."""
     return _call("axonn_linear_bwd_weight", M, N, K, layout, X, dY, dW, fp32_accumulate, stream, check)
+
+
+def axonn_linear_gemm_static(M, N, K, layout, first, second, out, fp32_accumulate=1, stream=None, check=True):
+    """out[M,N] = the product, split-K through the library's static scratch array (no allocation anywhere)."""
+    return _call("axonn_linear_gemm_static", M, N, K, layout, first, second, out, fp32_accumulate, stream, check)
+
+
+def axonn_linear_static_scratch_bytes() -> int:
+    return int(lib().axonn_linear_static_scratch_bytes())
 
 
 def axonn_transpose_bf16(rows, cols, src, dst, stream=None, check=True):

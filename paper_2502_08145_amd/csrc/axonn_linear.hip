@@ -2,7 +2,8 @@
 // Host side: argument checks, kernel-variant selection, launch.  No device memory is allocated
 // anywhere in this file, and the GEMM entry points never synchronise: split-K kernels exchange their
 // partial tiles through memory the caller registered (axonn_linear_set_workspace, which clears the
-// flag words synchronously).
+// flag words synchronously) or, for the one entry point made for callers that cannot allocate,
+// through a file-scope device array.
 #include "../../include/axonn_linear.h"
 
 #include <hip/hip_runtime.h>
@@ -191,6 +192,36 @@ static Scratch registered_scratch(size_t bytes_needed) {
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
     const Scratch& sc = g_scratch[dev];
     return (sc.partials && sc.partial_bytes >= bytes_needed) ? sc : Scratch{};
+}
+
+// The scratch area of the entry point for callers that cannot allocate: a device array of fixed size
+// that every GPU the library runs on holds from the moment the code object is loaded until the
+// process ends (zero-filled at load).  In host code the array's NAME is only a handle for
+// hipGetSymbolAddress; the address kernels and copies may use is looked up once per device, with that
+// device current, and kept in g_static_ptr.
+constexpr int kStaticSlots = 128;                           // 32 MiB of partial tiles
+constexpr size_t kStaticBytes = kFlagBytes + kStaticSlots * kSlotBytes;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticBytes];
+static unsigned char* g_static_ptr[kMaxDevices];
+static std::mutex g_static_mutex;
+
+// The current device's copy of the static area; .partials == nullptr if the look-up failed.
+static Scratch static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return Scratch{};
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return Scratch{};
+        }
+        g_static_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    return carve(g_static_ptr[dev], kStaticBytes);
 }
 
 static std::atomic<int> g_forced{-1};
@@ -475,8 +506,11 @@ static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layo
                        A, B, C, (int)K, (int)lda, (int)ldb, (int)ldc, tiles_m, tiles_n, group_m, sk);
 }
 
+// Where a call's split-K kernels find their scratch area.
+enum class ScratchFrom { Registered, Static };
+
 static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, const void* b, void* c,
-                  int fp32_accumulate, void* stream) {
+                  int fp32_accumulate, void* stream, ScratchFrom from = ScratchFrom::Registered) {
     const int rc = check_args(M, N, K, layout, a, b, c, fp32_accumulate);
     if (rc != AXONN_OK) return rc;
     if (M == 0 || N == 0) return AXONN_OK;
@@ -491,7 +525,10 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
         plan = cached_plan(M, N, K, layout, g_split_k_enabled.load(std::memory_order_relaxed) != 0);
     }
     if (const size_t need = split_bytes(plan)) {
-        if (!(scratch = registered_scratch(need)).partials) {
+        if (from == ScratchFrom::Static) {
+            // the static area has one size: a product whose plan needs more is refused, not re-planned
+            if (need > kStaticSlots * kSlotBytes || !(scratch = static_scratch()).partials) return AXONN_ERR_WORKSPACE;
+        } else if (!(scratch = registered_scratch(need)).partials) {
             if (forced >= 0) return AXONN_ERR_WORKSPACE;
             plan = cached_plan(M, N, K, layout, false);   // no area, or too small a one: the kernels that need none
         }
@@ -641,13 +678,20 @@ int axonn_linear_bwd_weight(int64_t M, int64_t N, int64_t K, int layout, const v
     return axonn::launch(M, N, K, layout, X, dY, dW, fp32_accumulate, stream);
 }
 
+int axonn_linear_gemm_static(int64_t M, int64_t N, int64_t K, int layout, const void* first, const void* second, void* out,
+                             int fp32_accumulate, void* stream) {
+    return axonn::launch(M, N, K, layout, first, second, out, fp32_accumulate, stream, axonn::ScratchFrom::Static);
+}
+
+size_t axonn_linear_static_scratch_bytes(void) { return axonn::kStaticBytes; }
+
 const char* axonn_status_string(int status) {
     switch (status) {
         case AXONN_OK: return "ok";
         case AXONN_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad dimension, layout or flag)";
         case AXONN_ERR_UNSUPPORTED: return "the forced kernel variant cannot run this shape";
         case AXONN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
-        case AXONN_ERR_WORKSPACE: return "no split-K scratch area of the size needed (none registered, or the registered one too small)";
+        case AXONN_ERR_WORKSPACE: return "no split-K scratch area of the size needed (none registered, the registered one too small, or the product's plan exceeds the static area)";
         default: return "unknown status";
     }
 }
@@ -689,7 +733,7 @@ int axonn_linear_call_plan(int64_t M, int64_t N, int64_t K, int layout, axonn_pl
 
 int axonn_linear_init(void) {
     axonn::raise_lds_limits_once();
-    return AXONN_OK;
+    return axonn::static_scratch().partials ? AXONN_OK : AXONN_ERR_WORKSPACE;
 }
 
 size_t axonn_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int layout) {
@@ -729,18 +773,24 @@ int axonn_linear_split_k_timeouts(uint64_t* count) {
     *count = 0;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= axonn::kMaxDevices) return AXONN_ERR_LAUNCH;
-    uint32_t* counter = nullptr;
+    uint32_t* counters[2] = {nullptr, nullptr};   // the registered area's and the static area's
     {
         std::lock_guard<std::mutex> lock(axonn::g_scratch_mutex);
-        if (axonn::g_scratch[dev].flags) counter = axonn::g_scratch[dev].timeouts();
+        if (axonn::g_scratch[dev].flags) counters[0] = axonn::g_scratch[dev].timeouts();
     }
-    if (!counter) return AXONN_OK;   // no area registered on this device
-    uint32_t v = 0;
-    if (hipMemcpy(&v, counter, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) {
-        (void)hipGetLastError();
-        return AXONN_ERR_LAUNCH;
+    {
+        std::lock_guard<std::mutex> lock(axonn::g_static_mutex);
+        if (axonn::g_static_ptr[dev]) counters[1] = axonn::carve(axonn::g_static_ptr[dev], axonn::kStaticBytes).timeouts();
     }
-    *count = v;
+    for (uint32_t* counter : counters) {
+        if (!counter) continue;   // no split-K kernel has used that area on this device
+        uint32_t v = 0;
+        if (hipMemcpy(&v, counter, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return AXONN_ERR_LAUNCH;
+        }
+        *count += v;
+    }
     return AXONN_OK;
 }
 
