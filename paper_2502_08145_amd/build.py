@@ -10,12 +10,15 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "axonn_linear.hip")
+CSRC = os.path.join(HERE, "csrc")
+# one translation unit per kernel family (the compile time is the kernels'), compiled side by side
+UNITS = ["axonn_linear.hip", "kernels_k64.hip", "kernels_ring_large.hip", "kernels_ring_small.hip", "kernels_edge.hip"]
 LIB_DIR = os.path.join(HERE, "lib")
+OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(LIB_DIR, "libaxonn_linear.so")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # hipcc must not form packed-fp32 instructions on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
@@ -36,7 +39,7 @@ def source_id() -> str:
     taken with, so that a stored counter reading can be told from one of an older kernel."""
     import hashlib
     h = hashlib.sha256()
-    files = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc")))
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC))
     files.append(os.path.join(os.path.dirname(HERE), "include", "axonn_linear.h"))
     for f in files:
         h.update(os.path.basename(f).encode())
@@ -44,9 +47,7 @@ def source_id() -> str:
     return h.hexdigest()[:16]
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    os.makedirs(LIB_DIR, exist_ok=True)
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, SRC, "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -56,7 +57,21 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+
+
+def build(verbose: bool = False, extra=(), units=None, out: str = LIB) -> str:
+    """Compile every translation unit (in parallel) and link them into the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    cc = hipcc()
+    units = list(units or UNITS)
+    objs = [os.path.join(OBJ_DIR, u.replace(".hip", ".o")) for u in units]
+    cmds = [[cc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, u), "-o", o] for u, o in zip(units, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda c: _run(c, verbose), cmds))
+    _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out], verbose)
+    return out
 
 
 if __name__ == "__main__":

@@ -14,8 +14,10 @@
 #include <mutex>
 #include <tuple>
 
-#include "gemm_mfma.hpp"
-#include "gemm_mfma16.hpp"
+#include <vector>
+
+#include "kernels.hpp"
+#include "gemm_mfma16.hpp"       // tile configurations only: the kernels are instantiated in kernels_*.hip
 #include "gemm_mfma16_k64.hpp"
 #include "gemm_edge.hpp"
 #include "comm_model.hpp"
@@ -51,107 +53,68 @@ __global__ __launch_bounds__(256) void gemm_naive_kernel(const uint16_t* __restr
 // ------------------------------------------------------------------------------------------
 // Variant table
 // ------------------------------------------------------------------------------------------
-// (A, B, C, K, lda, ldb, ldc, tiles_m, tiles_n, group_m, split-K state): leading dimensions in elements of
-// the operands as stored, so that a launch can cover a block of rows or columns of a larger product
-typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, int, int, int, int, int, int, SplitK);
-
 struct Variant {
     const char* name;
     int bm, bn, threads, lds_bytes, min_k;  // bm == 0: the naive kernel; min_k per K range
     int kstep;                       // K (per range) must be a multiple of this
     int splits;                      // K ranges per tile (1: no split-K)
-    int base;                        // index of the variant whose measured efficiency applies
+    bool k64;                        // the kernel with 64-k LDS stages
+    // Throughput with every CU busy, per layout (NN, NT, TN), N(0,1) data, in units of 1200 TFLOP/s.
+    // Regenerate with `python -m paper_2502_08145_amd.sweeps variant_eff`, which times every variant
+    // without split-K on full-chip shapes and prints these numbers.
+    double eff[3];
     tile_kernel_t fn[3];             // per layout
-    bool edge = false;               // the guarded MFMA kernel: any shape, launched through launch_edge
+    bool edge = false;               // the guarded MFMA kernel: any shape, launched through edge_kernel_launch
 };
 
-#define AXONN_TILE_VARIANT(NAME, BM, BN, WM, WN, SPLITS, BASE)                                       \
-    {                                                                                                \
-        NAME, BM, BN, TileCfg<BM, BN, WM, WN>::NT, TileCfg<BM, BN, WM, WN>::LDS_BYTES,               \
-            TileCfg<BM, BN, WM, WN>::MIN_K, KB, SPLITS, BASE, {                                      \
-            gemm_tile_kernel<BM, BN, WM, WN, true, false, (SPLITS > 1)>,                             \
-                gemm_tile_kernel<BM, BN, WM, WN, true, true, (SPLITS > 1)>,                          \
-                gemm_tile_kernel<BM, BN, WM, WN, false, false, (SPLITS > 1)>                         \
-        }                                                                                            \
-    }
-
-// the same on 16x16x32 MFMAs (two K-steps per loop iteration: K a multiple of 64)
-#define AXONN_TILE_VARIANT16(NAME, BM, BN, WM, WN, SPLITS, BASE)                                     \
-    {                                                                                                \
-        NAME, BM, BN, TileCfg16<BM, BN, WM, WN>::NT, TileCfg16<BM, BN, WM, WN>::LDS_BYTES,           \
-            TileCfg16<BM, BN, WM, WN>::MIN_K, 2 * KB, SPLITS, BASE, {                                \
-            gemm_tile_kernel16<BM, BN, WM, WN, true, false, (SPLITS > 1)>,                           \
-                gemm_tile_kernel16<BM, BN, WM, WN, true, true, (SPLITS > 1)>,                        \
-                gemm_tile_kernel16<BM, BN, WM, WN, false, false, (SPLITS > 1)>                       \
-        }                                                                                            \
-    }
-
-// the kernel with 64-k LDS stages (one barrier per 64 k), 2 x WN waves
-#define AXONN_TILE_VARIANT_K64(NAME, WN, SPLITS, BASE)                                               \
-    {                                                                                                \
-        NAME, 256, 256, 128 * WN, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, SPLITS, BASE, { \
-            gemm_tile_kernel_k64<WN, true, false, (SPLITS > 1)>, gemm_tile_kernel_k64<WN, true, true, (SPLITS > 1)>, \
-                gemm_tile_kernel_k64<WN, false, false, (SPLITS > 1)>                                 \
-        }                                                                                            \
-    }
-
-static const Variant g_variants[] = {
-    {"naive", 0, 0, 256, 0, 0, 1, 1, 0, {nullptr, nullptr, nullptr}},
-    AXONN_TILE_VARIANT("mfma_256x256", 256, 256, 2, 2, 1, 1),
-    AXONN_TILE_VARIANT("mfma_256x128", 256, 128, 2, 2, 1, 2),
-    AXONN_TILE_VARIANT("mfma_128x256", 128, 256, 2, 2, 1, 3),
-    AXONN_TILE_VARIANT("mfma_128x128", 128, 128, 2, 2, 1, 4),
-    AXONN_TILE_VARIANT("mfma_256x256_w8", 256, 256, 2, 4, 1, 5),
-    AXONN_TILE_VARIANT("mfma_256x128_w8", 256, 128, 2, 4, 1, 6),
-    AXONN_TILE_VARIANT("mfma_128x256_w8", 128, 256, 2, 4, 1, 7),
-    // split-K: 2 or 4 workgroups per 256x256 tile
-    AXONN_TILE_VARIANT("mfma_256x256_sk2", 256, 256, 2, 2, 2, 1),
-    AXONN_TILE_VARIANT("mfma_256x256_sk4", 256, 256, 2, 2, 4, 1),
-    AXONN_TILE_VARIANT("mfma_256x256_w8_sk2", 256, 256, 2, 4, 2, 5),
-    AXONN_TILE_VARIANT("mfma_256x256_w8_sk4", 256, 256, 2, 4, 4, 5),
-    // ... or per 128x128 tile (small shard shapes)
-    AXONN_TILE_VARIANT("mfma_128x128_sk2", 128, 128, 2, 2, 2, 4),
-    AXONN_TILE_VARIANT("mfma_128x128_sk4", 128, 128, 2, 2, 4, 4),
-    // 16x16x32 MFMAs
-    AXONN_TILE_VARIANT16("mfma16_256x256", 256, 256, 2, 2, 1, 8),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8", 256, 256, 2, 4, 1, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_sk2", 256, 256, 2, 2, 2, 8),
-    AXONN_TILE_VARIANT16("mfma16_256x256_sk4", 256, 256, 2, 2, 4, 8),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk2", 256, 256, 2, 4, 2, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk4", 256, 256, 2, 4, 4, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x128", 256, 128, 2, 2, 1, 10),
-    AXONN_TILE_VARIANT16("mfma16_128x256", 128, 256, 2, 2, 1, 11),
-    AXONN_TILE_VARIANT16("mfma16_128x256_w8", 128, 256, 2, 4, 1, 12),
-    AXONN_TILE_VARIANT16("mfma16_128x128", 128, 128, 2, 2, 1, 13),
-    AXONN_TILE_VARIANT16("mfma16_128x128_sk2", 128, 128, 2, 2, 2, 13),
-    AXONN_TILE_VARIANT16("mfma16_128x128_sk4", 128, 128, 2, 2, 4, 13),
-    // other numbers of K ranges (the kernels take the count at run time): 3 for outputs of 65-85 large
-    // tiles, ..., 8 for at most 32
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk3", 256, 256, 2, 4, 3, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk5", 256, 256, 2, 4, 5, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk6", 256, 256, 2, 4, 6, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk7", 256, 256, 2, 4, 7, 9),
-    AXONN_TILE_VARIANT16("mfma16_256x256_w8_sk8", 256, 256, 2, 4, 8, 9),
-    // 64-k LDS stages
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256", 2, 1, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk2", 2, 2, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk3", 2, 3, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk4", 2, 4, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_sk8", 2, 8, 14),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8", 4, 1, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk2", 4, 2, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk3", 4, 3, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk4", 4, 4, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk5", 4, 5, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk6", 4, 6, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk7", 4, 7, 15),
-    AXONN_TILE_VARIANT_K64("mfma16k64_256x256_w8_sk8", 4, 8, 15),
+// Kernel families: the 64-k-stage kernel (256 x 256, eight waves: the default wherever the output has
+// whole large tiles), the 32-k ring (the same tile for NT at very long K and TN with four and more K
+// ranges; the smaller tiles for outputs of few tiles), the guarded kernel.  Split-K variants of one
+// tile share one kernel (the number of K ranges is a run-time argument).
+static std::vector<Variant> make_variants() {
+    std::vector<Variant> v;
+    v.push_back({"naive", 0, 0, 256, 0, 0, 1, 1, false, {0, 0, 0}, {nullptr, nullptr, nullptr}});
+    auto ring = [&](const char* name, int bm, int bn, int wn, int splits, int lds, int min_k, double nn, double nt, double tn) {
+        Variant x{name, bm, bn, 128 * wn, lds, min_k, 2 * KB, splits, false, {nn, nt, tn}, {nullptr, nullptr, nullptr}};
+        for (int l = 0; l < 3; ++l)
+            x.fn[l] = (bm == 256 && bn == 256) ? ring_kernel_large(splits > 1, l) : ring_kernel_small(bm, bn, wn, splits > 1, l);
+        v.push_back(x);
+    };
+    auto k64 = [&](const char* name, int splits) {
+        Variant x{name, 256, 256, 512, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
+                  {1.17, 1.13, 1.15}, {nullptr, nullptr, nullptr}};
+        for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel(splits > 1, l);
+        v.push_back(x);
+    };
+    using L = TileCfg16<256, 256, 2, 4>;
+    ring("mfma16_256x256_w8", 256, 256, 4, 1, L::LDS_BYTES, L::MIN_K, 1.13, 1.06, 1.12);
+    static const char* const ring_sk[] = {"mfma16_256x256_w8_sk2", "mfma16_256x256_w8_sk3", "mfma16_256x256_w8_sk4", "mfma16_256x256_w8_sk5",
+                                          "mfma16_256x256_w8_sk6", "mfma16_256x256_w8_sk7", "mfma16_256x256_w8_sk8"};
+    for (int sp = 2; sp <= 8; ++sp) ring(ring_sk[sp - 2], 256, 256, 4, sp, L::LDS_BYTES, L::MIN_K, 1.13, 1.06, 1.12);
+    ring("mfma16_256x128", 256, 128, 2, 1, TileCfg16<256, 128, 2, 2>::LDS_BYTES, TileCfg16<256, 128, 2, 2>::MIN_K, 0.86, 0.78, 0.91);
+    ring("mfma16_128x256", 128, 256, 2, 1, TileCfg16<128, 256, 2, 2>::LDS_BYTES, TileCfg16<128, 256, 2, 2>::MIN_K, 0.95, 0.74, 0.92);
+    ring("mfma16_128x256_w8", 128, 256, 4, 1, TileCfg16<128, 256, 2, 4>::LDS_BYTES, TileCfg16<128, 256, 2, 4>::MIN_K, 0.93, 0.72, 0.97);
+    using S = TileCfg16<128, 128, 2, 2>;
+    ring("mfma16_128x128", 128, 128, 2, 1, S::LDS_BYTES, S::MIN_K, 0.85, 0.72, 0.90);
+    ring("mfma16_128x128_sk2", 128, 128, 2, 2, S::LDS_BYTES, S::MIN_K, 0.85, 0.72, 0.90);
+    ring("mfma16_128x128_sk4", 128, 128, 2, 4, S::LDS_BYTES, S::MIN_K, 0.85, 0.72, 0.90);
+    k64("mfma16k64_256x256_w8", 1);
+    static const char* const k64_sk[] = {"mfma16k64_256x256_w8_sk2", "mfma16k64_256x256_w8_sk3", "mfma16k64_256x256_w8_sk4", "mfma16k64_256x256_w8_sk5",
+                                         "mfma16k64_256x256_w8_sk6", "mfma16k64_256x256_w8_sk7", "mfma16k64_256x256_w8_sk8"};
+    for (int sp = 2; sp <= 8; ++sp) k64(k64_sk[sp - 2], sp);
     // guarded MFMA kernel: ragged shapes and the edge strips of ragged outputs
-    {"mfma16_edge_128x128", EdgeCfg::BM, EdgeCfg::BN, EdgeCfg::NT, EdgeCfg::LDS_BYTES, 1, 1, 1, 0, {nullptr, nullptr, nullptr}, true},
-};
-constexpr int kNumVariants = sizeof(g_variants) / sizeof(g_variants[0]);
-constexpr int kEdgeVariant = kNumVariants - 1;
-static bool is_guarded(int v) { return g_variants[v].bm == 0 || g_variants[v].edge; }
+    Variant e{"mfma16_edge_128x128", EdgeCfg::BM, EdgeCfg::BN, EdgeCfg::NT, EdgeCfg::LDS_BYTES, 1, 1, 1, false, {0, 0, 0}, {nullptr, nullptr, nullptr}};
+    e.edge = true;
+    v.push_back(e);
+    return v;
+}
+static const std::vector<Variant>& variants() {
+    static const std::vector<Variant> table = make_variants();
+    return table;
+}
+static int num_variants() { return (int)variants().size(); }
+static int edge_variant() { return num_variants() - 1; }
+static bool is_guarded(int v) { return variants()[v].bm == 0 || variants()[v].edge; }
 
 // Split-K scratch: one area per device.  Layout: kFlagBytes of flags (one 32-bit flag per slot, the
 // time-out counter in the last word), then slots of one 256x256 fp32 tile each.  The area is the
@@ -228,8 +191,8 @@ static std::atomic<int> g_forced{-1};
 static std::once_flag g_attr_once[kMaxDevices];   // the LDS limits are a per-device property of a kernel
 
 static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout) {
-    if (v < 0 || v >= kNumVariants || layout < 0 || layout > 2) return false;
-    const Variant& var = g_variants[v];
+    if (v < 0 || v >= num_variants() || layout < 0 || layout > 2) return false;
+    const Variant& var = variants()[v];
     if (var.bm == 0) return true;
     if (M <= 0 || N <= 0 || K <= 0) return false;
     if (var.edge) return ((M + var.bm - 1) / var.bm) * ((N + var.bn - 1) / var.bn) < ((int64_t)1 << 31);
@@ -249,30 +212,22 @@ static bool variant_supports(int v, int64_t M, int64_t N, int64_t K, int layout)
 // whole tile time, and a smaller tile moves more operand bytes per flop.  Pick the variant with the
 // smallest modelled time:
 //     rounds x tile area x (K per workgroup + fixed cost) / efficiency
-// where the efficiencies are throughputs measured on MI355X with every CU busy (N(0,1) data),
-// relative to the 4-wave 256x256 tile of each layout, and the fixed cost (pipeline fill, epilogue,
+// where the efficiencies are throughputs measured on MI355X with every CU busy (N(0,1) data, see
+// Variant::eff), and the fixed cost (pipeline fill, epilogue,
 // for split-K also the exchange of fp32 partial tiles) is expressed in units of k.
 // K-contiguous operands are the dearer ones to stage (64-byte row segments per load), which is
 // why NN likes a short A tile (128x256) and NT gains least from any of the smaller tiles.
 // Split-K turns an output of at most 128 tiles of 256x256 into a full round of the large tile.
 static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, bool allow_split) {
-    static const double eff[3][16] = {
-        /* variant:   naive 256x256 256x128 128x256 128x128, the 8-wave 256x256 256x128 128x256, then the
-         *            16x16x32 256x256 with 4 and 8 waves, 256x128, 128x256, 8-wave 128x256, 128x128,
-         *            the 64-k kernel with 4 and 8 waves */
-        /* NN */ {0.0, 1.00, 0.83, 0.90, 0.80, 1.06, 0.82, 0.86, 1.09, 1.13, 0.86, 0.95, 0.93, 0.85, 1.11, 1.17},
-        /* NT */ {0.0, 1.00, 0.79, 0.71, 0.70, 1.02, 0.79, 0.70, 1.05, 1.06, 0.78, 0.74, 0.72, 0.72, 1.12, 1.13},
-        /* TN */ {0.0, 1.00, 0.91, 0.90, 0.89, 1.06, 0.89, 0.95, 1.00, 1.12, 0.91, 0.92, 0.97, 0.90, 1.06, 1.15},
-    };
     constexpr double kFixedK = 128.0;
-    const Variant& var = g_variants[v];
-    if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || eff[layout][var.base] <= 0.0) return -1.0;
+    const Variant& var = variants()[v];
+    if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || var.eff[layout] <= 0.0) return -1.0;
     // The 64-k kernels hold two K-steps less in LDS than the 32-k ring; over very long K ranges the
     // workgroups behind one L2 drift further apart than that tolerates.  Measured with the final
     // epilogue: in NT the 64-k kernel is 4-5 % behind the ring at K = 32768 and 49152 (8192 x 8192
     // outputs) and ahead of it up to 24576; in NN and TN it stays 1-5 % ahead at those K.  The split-K
     // forms were compared up to K = 32768 only.
-    if (var.base == 14 || var.base == 15) {
+    if (var.k64) {
         if (var.splits == 1 ? (layout == AXONN_NT && K > 24576) : K > 32768) return -1.0;
     }
     const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
@@ -292,15 +247,14 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     const double fixed_small = var.splits == 2 ? 700.0 + 8.0 * tiles : 1300.0 + 25.0 * tiles;
     // large tiles: the partial tiles travel through HBM, (splits - 1) x 256 KB per tile written and
     // read back at 4-5 TB/s (0.1 us, or 4 units of k, per slot), and the reader of a tile takes its
-    // slots one after the other at one CU's rate (2.5 us, 100 units, per slot); the 4-wave
-    // kernels exchange more slowly (half as many waves keep stores and loads in flight)
-    const double fixed_large = (var.threads == 256 ? 512.0 : 0.0) + 4.0 * tiles * (var.splits - 1) + 100.0 * (var.splits - 1);
+    // slots one after the other at one CU's rate (2.5 us, 100 units, per slot)
+    const double fixed_large = 4.0 * tiles * (var.splits - 1) + 100.0 * (var.splits - 1);
     const double k_cost = (double)(K / var.splits) + kFixedK +
                           (var.splits == 1 ? 0.0 : var.bm * var.bn <= 128 * 128 ? fixed_small : fixed_large);
-    double e = eff[layout][var.base];
-    // the 8-wave 64-k kernel leads the 32-k ring in TN by 2-4 % in one range and in two (six clusters
-    // of transposing reads, streamed epilogue); with four ranges and more it measured 2-4 % behind
-    if (layout == AXONN_TN && var.base == 15 && var.splits >= 4) e *= 0.94;
+    double e = var.eff[layout];
+    // the 64-k kernel leads the 32-k ring in TN by 2-4 % in one range and in two (six clusters of
+    // transposing reads, streamed epilogue); with four ranges and more it measured 2-4 % behind
+    if (layout == AXONN_TN && var.k64 && var.splits >= 4) e *= 0.94;
     return rounds * var.bm * var.bn * k_cost / e;
 }
 
@@ -320,15 +274,15 @@ static double edge_time(int64_t m, int64_t n, int64_t K) {
 static int select_variant(int64_t M, int64_t N, int64_t K, int layout, bool allow_split, double* t_out = nullptr) {
     int best = 0;
     double best_t = 0;
-    for (int v = 1; v < kNumVariants; ++v) {
+    for (int v = 1; v < num_variants(); ++v) {
         const double t = model_time(v, M, N, K, layout, allow_split);
         if (t >= 0.0 && (best == 0 || t < best_t)) {
             best = v;
             best_t = t;
         }
     }
-    if (best == 0 && variant_supports(kEdgeVariant, M, N, K, layout)) {
-        best = kEdgeVariant;
+    if (best == 0 && variant_supports(edge_variant(), M, N, K, layout)) {
+        best = edge_variant();
         best_t = edge_time(M, N, K);
     }
     if (t_out) *t_out = best_t;
@@ -370,8 +324,8 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, int layout, bool allow_sp
             if (!is_guarded(v_tiles) && t_tiles + t_strips < t_one) {
                 const Plan inner = make_plan(mm, nm, K, layout, allow_split);
                 plan = inner;
-                if (nm != N) plan.part[plan.parts++] = Part{kEdgeVariant, mm, N - nm, 0, nm};
-                if (mm != M) plan.part[plan.parts++] = Part{kEdgeVariant, M - mm, N, mm, 0};
+                if (nm != N) plan.part[plan.parts++] = Part{edge_variant(), mm, N - nm, 0, nm};
+                if (mm != M) plan.part[plan.parts++] = Part{edge_variant(), M - mm, N, mm, 0};
             }
         }
         return plan;
@@ -436,14 +390,11 @@ static int check_args(int64_t M, int64_t N, int64_t K, int layout, const void* a
 }
 
 static void raise_lds_limits() {
-    for (int v = 1; v < kNumVariants; ++v)
+    for (const Variant& var : variants())
         for (int l = 0; l < 3; ++l)
-            if (g_variants[v].fn[l])
-                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(g_variants[v].fn[l]),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, g_variants[v].lds_bytes);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<true, false>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_edge_kernel<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, EdgeCfg::LDS_BYTES);
+            if (var.fn[l])
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(var.fn[l]), hipFuncAttributeMaxDynamicSharedMemorySize, var.lds_bytes);
+    edge_kernel_raise_lds_limit();
     (void)hipGetLastError();
 }
 
@@ -459,7 +410,7 @@ static void raise_lds_limits_once() {
 }
 
 static size_t split_bytes(const Part& p) {
-    const Variant& x = g_variants[p.variant];
+    const Variant& x = variants()[p.variant];
     return x.splits == 1 ? 0 : (size_t)((p.m / x.bm) * (p.n / x.bn) * (x.splits - 1)) * x.bm * x.bn * sizeof(float);
 }
 
@@ -471,26 +422,21 @@ static size_t split_bytes(const Plan& plan) {
 
 // workgroups of the launch over block `p`
 static int64_t part_workgroups(const Part& p) {
-    const Variant& var = g_variants[p.variant];
+    const Variant& var = variants()[p.variant];
     return ((p.m + var.bm - 1) / var.bm) * ((p.n + var.bn - 1) / var.bn) * var.splits;
 }
 
 // One kernel launch over the block `p` of the M x N output.
 static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layout, const uint16_t* A, const uint16_t* B,
                         uint16_t* C, const Scratch& scratch, hipStream_t s) {
-    const Variant& var = g_variants[p.variant];
+    const Variant& var = variants()[p.variant];
     const int64_t lda = layout == AXONN_TN ? M : K, ldb = layout == AXONN_NT ? K : N, ldc = N;
     A += layout == AXONN_TN ? p.row0 : p.row0 * K;
     B += layout == AXONN_NT ? p.col0 * K : p.col0;
     C += p.row0 * N + p.col0;
     if (var.edge) {
         const int tiles_n = (int)((p.n + var.bn - 1) / var.bn);
-        const dim3 grid((unsigned)part_workgroups(p)), block(var.threads);
-        switch (layout) {
-            case AXONN_NN: hipLaunchKernelGGL((gemm_edge_kernel<true, false>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
-            case AXONN_NT: hipLaunchKernelGGL((gemm_edge_kernel<true, true>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
-            default:       hipLaunchKernelGGL((gemm_edge_kernel<false, false>), grid, block, var.lds_bytes, s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n); break;
-        }
+        edge_kernel_launch(layout, (unsigned)part_workgroups(p), s, A, B, C, p.m, p.n, K, lda, ldb, ldc, tiles_n);
         return;
     }
     const int tiles_m = (int)(p.m / var.bm), tiles_n = (int)(p.n / var.bn);
@@ -539,7 +485,7 @@ static int launch(int64_t M, int64_t N, int64_t K, int layout, const void* a, co
     uint16_t* C = static_cast<uint16_t*>(c);
 
     (void)hipGetLastError();
-    if (g_variants[plan.part[0].variant].bm == 0) {
+    if (variants()[plan.part[0].variant].bm == 0) {
         const int64_t blocks = ((M + 15) / 16) * ((N + 15) / 16);
         const dim3 grid((unsigned)std::min<int64_t>(blocks, (int64_t)1 << 20));
         switch (layout) {
@@ -698,10 +644,10 @@ const char* axonn_status_string(int status) {
 
 int axonn_linear_version(void) { return 100; }
 
-int axonn_linear_num_variants(void) { return axonn::kNumVariants; }
+int axonn_linear_num_variants(void) { return axonn::num_variants(); }
 
 const char* axonn_linear_variant_name(int variant) {
-    return (variant >= 0 && variant < axonn::kNumVariants) ? axonn::g_variants[variant].name : nullptr;
+    return (variant >= 0 && variant < axonn::num_variants()) ? axonn::variants()[variant].name : nullptr;
 }
 
 int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout) {
@@ -886,7 +832,7 @@ int64_t axonn_comm_rank_grids(int64_t g_total, const axonn_comm_layer_t* layers,
 }
 
 int axonn_linear_force_variant(int variant) {
-    if (variant < -1 || variant >= axonn::kNumVariants) return AXONN_ERR_INVALID_ARG;
+    if (variant < -1 || variant >= axonn::num_variants()) return AXONN_ERR_INVALID_ARG;
     axonn::g_forced.store(variant, std::memory_order_relaxed);
     return AXONN_OK;
 }

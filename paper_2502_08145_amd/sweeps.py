@@ -2,6 +2,7 @@
 
     python -m paper_2502_08145_amd.sweeps peak_curve [--max 65536]
     python -m paper_2502_08145_amd.sweeps model_zoo [--tokens 2048]
+    python -m paper_2502_08145_amd.sweeps variant_eff
 
 peak_curve   square bf16 GEMMs 1024 ... 65536 in the three modes, the protocol of the paper's
              single-GPU GEMM benchmark (Sec. V-C: repeated runs, mean of the last three quarters),
@@ -10,6 +11,10 @@ model_zoo    the shard shapes of the paper's model table (Sec. V-A, the table of
              FFN 4h, fused QKV 3h) under every split of a weight's two dimensions by 1, 2, 4 or 8
              (Sec. IV-A: a weight is sharded over two of the grid's dimensions), forward,
              backward-data and backward-weight in their natural modes.
+
+variant_eff  every kernel variant without split-K, forced, on shapes that fill the chip a whole number of
+             times in all three modes; prints the throughputs in units of 1200 TFLOP/s, which is what
+             the library's selection model keeps per variant (Variant::eff in csrc/axonn_linear.hip).
 
 Operands are N(0,1) (activations, gradients) and N(0, 0.02^2) (weights) drawn on the device with a
 fixed seed: host generation of 65536^2 matrices would take minutes.  Output: one text line per
@@ -104,6 +109,38 @@ def model_zoo(args):
               f"{flops_sum / ms_sum / 1e9:9.1f}  {worst[1]} ({worst[0]:.0f} TFLOP/s)", flush=True)
 
 
+def variant_eff(args):
+    """Efficiencies of the selection model: mean over the shapes of TFLOP/s / 1200, per variant and mode."""
+    gen = torch.Generator(device="cuda").manual_seed(250208148)
+    shapes = [(4096, 4096, 4096), (8192, 8192, 8192), (4096, 16384, 2048), (2048, 16384, 4096)]
+    names = [B.variant_name(v) for v in range(B.num_variants())]
+    rows = {}
+    for M, N, K in shapes:
+        a = randn_bf16((M, K), 1.0, gen)
+        b = randn_bf16((K, N), 1.0, gen)
+        c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        for layout in ("NN", "NT", "TN"):
+            x = a.t().contiguous() if layout == "TN" else a
+            y = b.t().contiguous() if layout == "NT" else b
+            for v, name in enumerate(names):
+                if v == 0 or "_sk" in name or "edge" in name or not B.variant_supports(v, M, N, K, layout):
+                    continue
+                B.force_variant(v)
+                try:
+                    ms = time_gemm("fwd", M, N, K, layout, x, y, c, 24, warm=6)
+                finally:
+                    B.force_variant(-1)
+                tf = 2.0 * M * N * K / ms / 1e9
+                rows.setdefault(name, {}).setdefault(layout, []).append(tf)
+                print(f"{M:6d} {N:6d} {K:6d} {layout} {name:<24s} {ms * 1e3:9.1f} us {tf:8.1f} TFLOP/s", flush=True)
+            del x, y
+        del a, b, c
+    print("variant                    eff NN   NT   TN   (TFLOP/s / 1200, mean over the shapes)")
+    for name, d in rows.items():
+        e = [sum(d[l]) / len(d[l]) / 1200.0 for l in ("NN", "NT", "TN")]
+        print(f"{name:<26s} {e[0]:6.2f} {e[1]:4.2f} {e[2]:4.2f}")
+
+
 def parse_smi(text):
     """(socket power in W or None, [shader clock of each XCD in MHz]) from the text of `amd-smi metric -c -p`."""
     power = re.search(r"SOCKET_POWER:\s*(\d+)\s*W", text)
@@ -124,13 +161,14 @@ def main(argv=None):
     z = sub.add_parser("model_zoo")
     z.add_argument("--tokens", type=int, default=2048)
     z.add_argument("--verbose", action="store_true")
+    sub.add_parser("variant_eff")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("sweeps: no GPU visible")
     B.lib()
     torch.cuda.set_device(0)
     B.register_workspace()          # the library allocates nothing: split-K scratch is ours to provide
-    {"peak_curve": peak_curve, "model_zoo": model_zoo}[args.cmd](args)
+    {"peak_curve": peak_curve, "model_zoo": model_zoo, "variant_eff": variant_eff}[args.cmd](args)
 
 
 if __name__ == "__main__":

@@ -86,14 +86,15 @@ def test_variant_table_and_selection():
             assert not B.variant_supports(v, 100, 200, 300, lay)
             assert B.variant_supports(v, 1024, 1024, 64 * 840, lay)          # 840 = lcm(1..8) K ranges
             assert not B.variant_supports(v, 1024, 1024, 1000, lay)
-            assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 32
-            assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS ring
+            assert not B.variant_supports(v, 1024, 1024, 200, lay)     # K must be a multiple of 64
+            assert not B.variant_supports(v, 1024, 1024, 64 * 5 + 32, lay)
+            assert not B.variant_supports(v, 1024, 1024, 64, lay)      # and long enough to fill the LDS buffers
             tail = names[v].rsplit("_", 1)[-1]
             splits = int(tail[2:]) if tail.startswith("sk") else 1
             assert B.variant_supports(v, 256, 256, 256 * splits, lay)   # per K range
-            kstep = 64 if names[v].startswith("mfma16") else 32         # the 16x16x32 kernels take K-steps in pairs
-            assert B.variant_supports(v, 256, 256, 256 * splits + kstep * splits, lay)
-            assert not B.variant_supports(v, 256, 256, 256 * splits + 32, lay) or (kstep == 32 and splits == 1)
+            assert names[v].startswith("mfma16")                        # one MFMA shape: 16x16x32, K taken 64 at a time
+            assert B.variant_supports(v, 256, 256, 256 * splits + 64 * splits, lay)
+            assert not B.variant_supports(v, 256, 256, 256 * splits + 32, lay)
             # split-K keeps (splits - 1) fp32 partial tiles per output tile in a 64 MiB scratch area
             # with 1023 flags
             bm, bn = (int(x) for x in names[v].split("_")[1].split("x"))

@@ -76,8 +76,8 @@ def splits_of(v):
 
 
 def kstep_of(v):
-    """K granularity of a variant: the 16x16x32 kernels consume K-steps of 32 in pairs."""
-    return 64 if B.variant_name(v).startswith("mfma16") else 32
+    """K granularity of a variant: every tile kernel consumes K 64 at a time."""
+    return 64
 
 
 def usable(v, M, N, K, layout):
@@ -204,28 +204,27 @@ def test_k_zero_gives_zero_and_empty_outputs_are_ok():
 # ------------------------------------------------------------------ every tile kernel, several tiles
 @pytest.mark.parametrize("layout", LAYOUTS)
 def test_every_tile_variant_against_oracle(oracle_mod, layout):
-    # 3 x 3 tiles of 256 (6 x 6 of 128), 13 K-steps of 32 per workgroup: multi-tile, the LDS ring
-    # wraps twice; split-K variants get 13 steps per K range (9 tiles x splits workgroups is not a
+    # 3 x 3 tiles of 256 (6 x 6 of 128), 7 K-steps of 64 per workgroup: multi-tile, the LDS ring
+    # wraps twice; split-K variants get 7 steps per K range (9 tiles x splits workgroups is not a
     # multiple of 8: the plain workgroup -> tile mapping)
     M, N = 768, 768
     for splits in range(1, 9):
-        for kstep in (32, 64):   # 13 steps of 32, or 14 for the kernels that take them in pairs
-            K = (416 if kstep == 32 else 448) * splits
-            a = synth.normal_bf16(31 + splits + kstep, (M, K))
-            b = synth.normal_bf16(32 + splits + kstep, (K, N), 0.02)
-            A, Bm = store(a, b, layout)
-            ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
-            ran = 0
-            for v in tile_variants(layout):
-                if splits_of(v) != splits or kstep_of(v) != kstep:
-                    continue
-                assert B.variant_supports(v, M, N, K, layout)
-                got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
-                nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
-                # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
-                assert nw < 4e-3, (B.variant_name(v), nw)
-                ran += 1
-            assert ran >= 2 or (splits in (3, 5, 6, 7, 8) and ran == (kstep == 64))
+        K = 448 * splits
+        a = synth.normal_bf16(31 + splits, (M, K))
+        b = synth.normal_bf16(32 + splits, (K, N), 0.02)
+        A, Bm = store(a, b, layout)
+        ref = oracle_mod.gemm(M, N, K, layout, A, Bm)
+        ran = 0
+        for v in tile_variants(layout):
+            if splits_of(v) != splits:
+                continue
+            assert B.variant_supports(v, M, N, K, layout)
+            got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
+            nw, ew = U.assert_close(got, ref, f"{B.variant_name(v)} {layout}")
+            # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
+            assert nw < 4e-3, (B.variant_name(v), nw)
+            ran += 1
+        assert ran == {1: 6, 2: 3, 4: 3}.get(splits, 2), (splits, ran)
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
@@ -250,7 +249,7 @@ def test_split_k_xcd_mapping_and_repeated_launches(oracle_mod, layout):
                 got = run_gpu("bwd_data", M, N, K, layout, A, Bm, variant=v)
                 assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
             ran += 1
-    assert ran >= 11
+    assert ran == 16
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
@@ -274,7 +273,7 @@ def test_split_k_long_k_one_range_per_xcd_pair(oracle_mod, layout, shape):
             got = run_gpu("fwd", M, N, K, layout, A, Bm, variant=v)
             assert np.array_equal(got, want), f"{B.variant_name(v)} {layout} launch {rep}"
         ran += 1
-    assert ran == 6
+    assert ran == 2
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
@@ -284,8 +283,8 @@ def test_shortest_k_and_single_tile(oracle_mod, layout):
     # never runs), and one step more
     M = N = 256
     for v in tile_variants(layout):
-        kmin = next(k for k in range(32, 4096, 32) if B.variant_supports(v, M, N, k, layout))
-        assert not B.variant_supports(v, M, N, kmin - 32, layout)
+        kmin = next(k for k in range(64, 4096, 64) if B.variant_supports(v, M, N, k, layout))
+        assert not B.variant_supports(v, M, N, kmin - 64, layout) and not B.variant_supports(v, M, N, kmin + 32, layout)
         for K in (kmin, kmin + kstep_of(v) * splits_of(v)):
             a = synth.normal_bf16(41 + K, (M, K))
             b = synth.normal_bf16(42 + K, (K, N))
@@ -777,8 +776,8 @@ def test_panel_larger_than_4_gib(oracle_mod):
     ii = rng.integers(0, M, 96).astype(np.int64)
     jj = rng.integers(0, N, 96).astype(np.int64)
     want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, "TN", A, Bm, ii, jj))
-    for v in (-1, [B.variant_name(x) for x in range(B.num_variants())].index("mfma16k64_256x256"),
-              [B.variant_name(x) for x in range(B.num_variants())].index("mfma_256x256_w8")):
+    for v in (-1, [B.variant_name(x) for x in range(B.num_variants())].index("mfma16k64_256x256_w8"),
+              [B.variant_name(x) for x in range(B.num_variants())].index("mfma16_256x256_w8")):
         got = run_gpu("bwd_weight", M, N, K, "TN", A, Bm, variant=v)
         assert np.array_equal(got[ii, jj], want), f"variant {v}"
 
