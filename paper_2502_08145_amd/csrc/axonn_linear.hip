@@ -19,6 +19,7 @@
 #include "kernels.hpp"
 #include "gemm_mfma16.hpp"       // tile configurations only: the kernels are instantiated in kernels_*.hip
 #include "gemm_mfma16_k64.hpp"
+#include "gemm_mfma16_k64p.hpp"
 #include "gemm_edge.hpp"
 #include "comm_model.hpp"
 #include "transpose.hpp"
@@ -65,6 +66,7 @@ struct Variant {
     double eff[3];
     tile_kernel_t fn[3];             // per layout
     bool edge = false;               // the guarded MFMA kernel: any shape, launched through edge_kernel_launch
+    int resident = 0;                // > 0: a grid of at most this many workgroups walks the tiles (one per compute unit)
 };
 
 // Kernel families: the 64-k-stage kernel (256 x 256, eight waves: the default wherever the output has
@@ -99,6 +101,13 @@ static std::vector<Variant> make_variants() {
     ring("mfma16_128x128_sk2", 128, 128, 2, 2, S::LDS_BYTES, S::MIN_K, 0.85, 0.72, 0.90);
     ring("mfma16_128x128_sk4", 128, 128, 2, 4, S::LDS_BYTES, S::MIN_K, 0.85, 0.72, 0.90);
     k64("mfma16k64_256x256_w8", 1);
+    {
+        Variant x{"mfma16k64p_256x256_w8", 256, 256, 512, TileCfgK64P::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, 1, true,
+                  {1.17, 1.13, 1.17}, {nullptr, nullptr, nullptr}};
+        for (int l = 0; l < 3; ++l) x.fn[l] = k64p_kernel(l);
+        x.resident = TileCfgK64P::MAX_WORKGROUPS;
+        v.push_back(x);
+    }
     static const char* const k64_sk[] = {"mfma16k64_256x256_w8_sk2", "mfma16k64_256x256_w8_sk3", "mfma16k64_256x256_w8_sk4", "mfma16k64_256x256_w8_sk5",
                                          "mfma16k64_256x256_w8_sk6", "mfma16k64_256x256_w8_sk7", "mfma16k64_256x256_w8_sk8"};
     for (int sp = 2; sp <= 8; ++sp) k64(k64_sk[sp - 2], sp);
@@ -230,6 +239,10 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     if (var.k64) {
         if (var.splits == 1 ? (layout == AXONN_NT && K > 24576) : K > 32768) return -1.0;
     }
+    // The resident-workgroup form of the 64-k kernel: measured against one workgroup per tile in the
+    // benchmark's sequence, 1.3-1.9 % less time for the TN products of three and four tiles per compute
+    // unit, +-1 % for NN, 1.6 % MORE for NT with two tiles and 2.5 % more with a single tile.
+    if (var.resident > 0 && !(layout == AXONN_TN && (M / var.bm) * (N / var.bn) >= 3 * var.resident)) return -1.0;
     const int64_t wgs = (M / var.bm) * (N / var.bn) * var.splits;
     // Every CU works through ceil(wgs / 256) workgroups (two small tiles resident on one CU run
     // side by side at half speed each, which comes to the same).  A last round that fills only
@@ -237,7 +250,7 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // power and bandwidth): measured about 0.6 + 0.4 f of a full round (0.61 at 4 workgroups,
     // 0.78 at 128, 0.87 at 144).
     const int64_t full = wgs / 256, rest = wgs % 256;
-    // readers and writers of a tile run side by side: one round (two 128x128 workgroups fit a CU)
+    // readers and writers of a tile should run side by side: one round of large tiles, two of small ones
     if (var.splits > 1 && wgs > (var.bm * var.bn <= 128 * 128 ? 512 : 256)) return -1.0;
     const double rounds = (double)full + (rest ? 0.6 + 0.4 * (double)rest / 256.0 : 0.0);
     // the exchange of a small tile is latency: the reader takes the partial tiles one after the
@@ -448,7 +461,8 @@ static void launch_part(const Part& p, int64_t M, int64_t N, int64_t K, int layo
         if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;   // flags start at 0
         sk = SplitK{scratch.partials, scratch.flags, scratch.timeouts(), epoch, var.splits};
     }
-    hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)(tiles * var.splits)), dim3(var.threads), var.lds_bytes, s,
+    const int64_t grid = var.resident > 0 ? std::min<int64_t>(tiles, var.resident) : tiles * var.splits;
+    hipLaunchKernelGGL(var.fn[layout], dim3((unsigned)grid), dim3(var.threads), var.lds_bytes, s,
                        A, B, C, (int)K, (int)lda, (int)ldb, (int)ldc, tiles_m, tiles_n, group_m, sk);
 }
 

@@ -81,6 +81,14 @@ struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks 
         voff[0] += 128;
         voff[1] += 128;
     }
+    // The window back to k = 0 (it has advanced `k_bytes`) of the panel rows that start at row0.
+    __device__ __forceinline__ void retarget(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int wave, uint32_t k_bytes) {
+#pragma unroll
+        for (int c = 0; c < QL; ++c)
+            base[c] = reinterpret_cast<const uint8_t*>(P) + (size_t)(row0 + 8 * (QL * wave + c)) * ld_bytes;
+        voff[0] -= k_bytes;
+        voff[1] -= k_bytes;
+    }
     template <int S>
     __device__ __forceinline__ Cursor cursor(uint32_t buf) const {
         return Cursor{raddr[S] + buf};
@@ -118,6 +126,10 @@ struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32
     }
     __device__ __forceinline__ void advance() {
         in.base += 2 * in.kstep_bytes;   // 64-bit: panels may exceed 4 GB
+    }
+    // The window back to k = 0 of the panel rows (m or n) that start at row0.
+    __device__ __forceinline__ void retarget(const uint16_t* P, int64_t row0, uint32_t ld_bytes, int wave, uint32_t /*k_bytes*/) {
+        in.base = reinterpret_cast<const uint8_t*>(P) + (size_t)row0 * 2 + (size_t)(Inner::KR * Inner::QL * wave) * ld_bytes;
     }
     template <int S>
     __device__ __forceinline__ Cursor cursor(uint32_t buf) const {

@@ -33,6 +33,10 @@ def short(name: str) -> str:
         wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
         return f"mfma16k64_256x256{'_w8' if wn == '4' else ''}{'_sk' if split == 'true' else ''}/{lay}"
+    m = re.search(r"gemm_tile_kernel_k64p<(true|false), (true|false)>", name)
+    if m:
+        lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get(m.groups(), "??")
+        return f"mfma16k64p_256x256_w8/{lay}"
     if "transpose_tile_kernel" in name:
         return "transpose_tile"
     if "gemm_naive_kernel" in name:

@@ -224,7 +224,7 @@ def test_every_tile_variant_against_oracle(oracle_mod, layout):
             # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
             assert nw < 4e-3, (B.variant_name(v), nw)
             ran += 1
-        assert ran == {1: 6, 2: 3, 4: 3}.get(splits, 2), (splits, ran)
+        assert ran == {1: 7, 2: 3, 4: 3}.get(splits, 2), (splits, ran)
     assert B.axonn_linear_split_k_timeouts() == 0
 
 
