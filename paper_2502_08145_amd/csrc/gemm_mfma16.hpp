@@ -31,6 +31,10 @@ struct TileCfg16 {
     static constexpr int TM = BM / WM, TN = BN / WN;        // wave tile
     static constexpr int MI = TM / 16, NI = TN / 16;        // 16x16 blocks per wave tile
     static constexpr int STAGE_BYTES = (BM + BN) * KB * 2;
+    // (128 x 128: six stages are 96 KB, one workgroup per compute unit.  Five stages, 80 KB, two per unit,
+    // measured 5-17 % faster in NN and TN on outputs of 512 and more small tiles, which the planner gives
+    // to the large tile anyway, and 8-10 % slower on the outputs of few tiles and long K that it is
+    // picked for.)
     static constexpr int NS = (BM + BN == 512) ? 5 : 6;
     static constexpr int RING_BYTES = NS * STAGE_BYTES;
     static constexpr int EPI_BYTES = BM * BN * 2;
@@ -258,7 +262,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_tile_kernel16(
 
 #define AXONN_FENCE() __builtin_amdgcn_sched_barrier(0)
     auto mfma = [&](auto buf_c, auto idx_c) __attribute__((always_inline)) {
-        constexpr int BUF = decltype(buf_c)::value, I = decltype(idx_c)::value / NI, J = decltype(idx_c)::value % NI;
+        // block rows in order, the blocks of a row back and forth: from one MFMA to the next exactly one
+        // operand changes (less toggling on the operand buses of a power-limited chip)
+        constexpr int BUF = decltype(buf_c)::value, I = decltype(idx_c)::value / NI, J0 = decltype(idx_c)::value % NI;
+        constexpr int J = (I & 1) ? NI - 1 - J0 : J0;
         acc[I][J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[BUF][J].get(), fa[BUF][I].get(), acc[I][J], 0, 0, 0);
     };
     auto mfma_range = [&](auto buf_c, auto lo_c, auto hi_c) __attribute__((always_inline)) {

@@ -97,7 +97,11 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel_k64p(
     auto mfma_range = [&](auto s_c, auto lo_c, auto hi_c) __attribute__((always_inline)) {
         constexpr int S = decltype(s_c)::value, LO = decltype(lo_c)::value, HI = decltype(hi_c)::value;
         static_for<HI - LO>([&](auto d) __attribute__((always_inline)) {
-            constexpr int I = (LO + decltype(d)::value) / NI, J = (LO + decltype(d)::value) % NI;
+            // block rows in order, the blocks of a row back and forth: from one MFMA to the next exactly one
+            // operand changes (0.3-0.5 % on the benchmark step in alternating runs: less toggling on the
+            // operand buses of a power-limited chip)
+            constexpr int I = (LO + decltype(d)::value) / NI, J0 = (LO + decltype(d)::value) % NI;
+            constexpr int J = (I & 1) ? NI - 1 - J0 : J0;
             acc[I][J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[S][J].get(), fa[S][I].get(), acc[I][J], 0, 0, 0);
         });
     };
