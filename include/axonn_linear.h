@@ -172,8 +172,29 @@ int axonn_linear_tune(int op, int64_t M, int64_t N, int64_t K, const void *first
 /* The remembered result for (op, M, N, K): returns 1 and fills *result, 0 if that product has not
  * been tuned in this process, AXONN_ERR_INVALID_ARG on a bad argument.  Host only. */
 int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_result_t *result);
+/* Remember `*result` under (op, M, N, K) as if the tuner had measured it (a caller that keeps its
+ * tuning results across runs, or a test).  AXONN_OK or AXONN_ERR_INVALID_ARG.  Host only. */
+int axonn_linear_tuned_set(int op, int64_t M, int64_t N, int64_t K, const axonn_tune_result_t *result);
 /* Forget all remembered results. */
 void axonn_linear_tune_reset(void);
+
+/* Run a product in its tuned mode (Sec. IV-C: "keep the fastest for the rest of training").  `op`,
+ * `first`, `second`, `out` as for axonn_linear_tune: the operands as the method caches them (natural
+ * mode).  The mode is the remembered best_layout_all_in of (op, M, N, K), or the natural mode if the
+ * product has not been tuned.  Operands which that mode wants stored the other way:
+ *   first             re-stored into `scratch` by this call, on `stream` (it changes with every call);
+ *   second            taken from `second_restored` if that is not NULL -- a transposed copy
+ *                     ([N,K] for fwd, [K,N] for bwd_data, [N,K] for bwd_weight) that the caller made
+ *                     with axonn_transpose_bf16 and keeps up to date, the way to hold a weight (it
+ *                     changes once per optimiser step) -- else re-stored into `scratch` by this call.
+ * `scratch`: DEVICE memory, 256-byte aligned, caller-owned; M*K*2 rounded up to 256 plus K*N*2 bytes
+ * cover every case; if it is too small for what the tuned mode needs, the product runs in its
+ * natural mode, which needs none.  *layout_used (may be NULL) receives the mode that ran.  Enqueues
+ * on `stream` and returns; allocates nothing.  Return codes of axonn_linear_fwd. */
+int axonn_linear_tuned_call(int op, int64_t M, int64_t N, int64_t K,
+                            const void *first, const void *second, void *out,
+                            const void *second_restored, void *scratch, size_t scratch_bytes,
+                            int fp32_accumulate, void *stream, int *layout_used);
 
 /* ---- communication performance model (Sec. IV-B, Eq. 1-7); host only, no GPU is touched -------- */
 

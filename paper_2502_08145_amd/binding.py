@@ -28,7 +28,7 @@ EXPORTS = (
     "axonn_linear_force_variant",
     "axonn_linear_init", "axonn_linear_set_split_k", "axonn_linear_split_k_timeouts",
     "axonn_linear_workspace_bytes", "axonn_linear_set_workspace", "axonn_transpose_bf16",
-    "axonn_linear_tune", "axonn_linear_tuned", "axonn_linear_tune_reset",
+    "axonn_linear_tune", "axonn_linear_tuned", "axonn_linear_tune_reset", "axonn_linear_tuned_set", "axonn_linear_tuned_call",
     "axonn_comm_group_bandwidths", "axonn_comm_layer_time", "axonn_comm_rank_grids",
 )
 
@@ -118,6 +118,11 @@ def lib() -> ctypes.CDLL:
         L.axonn_linear_tune.restype = ci
         L.axonn_linear_tuned.argtypes = [ci, i64, i64, i64, ctypes.POINTER(TuneResult)]
         L.axonn_linear_tuned.restype = ci
+        L.axonn_linear_tuned_set.argtypes = [ci, i64, i64, i64, ctypes.POINTER(TuneResult)]
+        L.axonn_linear_tuned_set.restype = ci
+        L.axonn_linear_tuned_call.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.c_size_t, ci, vp,
+                                              ctypes.POINTER(ci)]
+        L.axonn_linear_tuned_call.restype = ci
         L.axonn_linear_tune_reset.argtypes = []
         L.axonn_linear_tune_reset.restype = None
         dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)
@@ -342,6 +347,29 @@ def axonn_linear_tuned(op, M, N, K):
     if rc < 0:
         raise AxonnError(rc, "axonn_linear_tuned")
     return res.as_dict() if rc == 1 else None
+
+
+def axonn_linear_tuned_set(op, M, N, K, best_layout_all_in, best_layout=None) -> None:
+    """Remember a tuning result for this product (modes by name or number)."""
+    res = TuneResult()
+    res.best_layout_all_in = _layout(best_layout_all_in)
+    res.best_layout = _layout(best_layout_all_in if best_layout is None else best_layout)
+    rc = lib().axonn_linear_tuned_set(OP_INDEX[op] if isinstance(op, str) else int(op), M, N, K, ctypes.byref(res))
+    if rc != 0:
+        raise AxonnError(rc, "axonn_linear_tuned_set")
+
+
+def axonn_linear_tuned_call(op, M, N, K, first, second, out, second_restored=None, scratch=None, fp32_accumulate=1,
+                            stream=None, check=True):
+    """Run the product in its tuned mode; returns the mode that ran (0 NN, 1 NT, 2 TN)."""
+    used = ctypes.c_int(-1)
+    sp, sb = (0, 0) if scratch is None else (scratch.data_ptr(), scratch.numel() * scratch.element_size())
+    rc = lib().axonn_linear_tuned_call(OP_INDEX[op] if isinstance(op, str) else int(op), M, N, K, _ptr(first), _ptr(second),
+                                       _ptr(out), _ptr(second_restored), sp, sb, int(fp32_accumulate), _stream(stream),
+                                       ctypes.byref(used))
+    if check and rc != 0:
+        raise AxonnError(rc, "axonn_linear_tuned_call")
+    return used.value if rc == 0 else rc
 
 
 def axonn_linear_tune_reset() -> None:

@@ -618,6 +618,62 @@ int axonn_linear_tuned(int op, int64_t M, int64_t N, int64_t K, axonn_tune_resul
     return 1;
 }
 
+int axonn_linear_tuned_set(int op, int64_t M, int64_t N, int64_t K, const axonn_tune_result_t* result) {
+    if (op < 0 || op > 2 || !result || M <= 0 || N <= 0 || K <= 0 || result->best_layout < 0 || result->best_layout > 2 ||
+        result->best_layout_all_in < 0 || result->best_layout_all_in > 2)
+        return AXONN_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(axonn::g_tuned_mutex);
+    axonn::g_tuned[std::make_tuple(op, M, N, K)] = *result;
+    return AXONN_OK;
+}
+
+int axonn_linear_tuned_call(int op, int64_t M, int64_t N, int64_t K, const void* first, const void* second, void* out,
+                            const void* second_restored, void* scratch, size_t scratch_bytes, int fp32_accumulate,
+                            void* stream, int* layout_used) {
+    using namespace axonn;
+    if (op < 0 || op > 2) return AXONN_ERR_INVALID_ARG;
+    const int nat = op;
+    int rc = check_args(M, N, K, nat, first, second, out, fp32_accumulate);
+    if (rc != AXONN_OK) return rc;
+    if (scratch_bytes && (!scratch || (reinterpret_cast<uintptr_t>(scratch) & 255))) return AXONN_ERR_INVALID_ARG;
+    if (second_restored && (reinterpret_cast<uintptr_t>(second_restored) & 15)) return AXONN_ERR_INVALID_ARG;
+    int mode = nat;
+    {
+        std::lock_guard<std::mutex> lock(g_tuned_mutex);
+        const auto it = g_tuned.find(std::make_tuple(op, M, N, K));
+        if (it != g_tuned.end()) mode = it->second.best_layout_all_in;
+    }
+    bool tf = first_is_mk(mode) != first_is_mk(nat), ts = second_is_kn(mode) != second_is_kn(nat);
+    const size_t first_bytes = (((size_t)M * K * 2) + 255) & ~(size_t)255, second_bytes = (size_t)K * N * 2;
+    const size_t need = (tf ? first_bytes : 0) + ((ts && !second_restored) ? second_bytes : 0);
+    if (need > scratch_bytes || M == 0 || N == 0 || K == 0) {   // no room to re-store: the natural mode needs none
+        mode = nat;
+        tf = ts = false;
+    }
+    const void* a = first;
+    const void* b = second;
+    char* free_ptr = static_cast<char*>(scratch);
+    if (tf) {
+        const int64_t rows = first_is_mk(nat) ? M : K, cols = first_is_mk(nat) ? K : M;
+        rc = axonn_transpose_bf16(rows, cols, first, free_ptr, stream);
+        if (rc != AXONN_OK) return rc;
+        a = free_ptr;
+        free_ptr += first_bytes;
+    }
+    if (ts) {
+        if (second_restored) {
+            b = second_restored;
+        } else {
+            const int64_t rows = second_is_kn(nat) ? K : N, cols = second_is_kn(nat) ? N : K;
+            rc = axonn_transpose_bf16(rows, cols, second, free_ptr, stream);
+            if (rc != AXONN_OK) return rc;
+            b = free_ptr;
+        }
+    }
+    if (layout_used) *layout_used = mode;
+    return launch(M, N, K, mode, a, b, out, fp32_accumulate, stream);
+}
+
 void axonn_linear_tune_reset(void) {
     std::lock_guard<std::mutex> lock(axonn::g_tuned_mutex);
     axonn::g_tuned.clear();

@@ -849,3 +849,47 @@ def test_tuner_times_all_modes_and_leaves_the_right_product(oracle_mod, op):
     B.axonn_linear_tune_reset()
     res0 = B.axonn_linear_tune(op, M, N, K, a, b, c, None)
     assert res0["best_layout"] == nat_i and sorted(us > 0 for us in res0["gemm_us"]) == [False, False, True]
+
+
+@pytest.mark.parametrize("op", ["fwd", "bwd_data", "bwd_weight"])
+def test_tuned_call_runs_the_product_in_the_remembered_mode(oracle_mod, op):
+    """Sec. IV-C, second half: once a mode has been chosen for a product it is the mode that runs.  Every
+    mode is set as the remembered winner in turn; the call re-stores what that mode wants transposed (the
+    first operand per call, the second from a copy the caller holds, or per call when it holds none) and
+    the output is the product all the same."""
+    T, d_in, d_out = 512, 768, 1024
+    t = synth.fc_layer_tensors(T, d_in, d_out, synth.BASE_SEED + 810)
+    g = next(x for x in synth.fc_layer_gemms(T, d_in, d_out, "fc") if x["op"] == op)
+    M, N, K, nat = g["M"], g["N"], g["K"], g["layout"]
+    A, Bm = synth.operands_for(op, nat, t)
+    ref = oracle_mod.gemm(M, N, K, nat, A, Bm)
+    a, b = U.to_device(A), U.to_device(Bm)
+    b_t = torch.empty((Bm.shape[1], Bm.shape[0]), dtype=torch.bfloat16, device="cuda")
+    B.axonn_transpose_bf16(Bm.shape[0], Bm.shape[1], b, b_t)       # the copy a caller would hold of a weight
+    scratch = torch.empty(((M * K * 2 + 255) // 256 * 256 + K * N * 2,), dtype=torch.uint8, device="cuda")
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    B.axonn_linear_tune_reset()
+    try:
+        c.view(torch.int16).fill_(0x7FC0)
+        assert B.axonn_linear_tuned_call(op, M, N, K, a, b, c, None, scratch) == B.LAYOUTS[nat]   # not tuned: natural mode
+        torch.cuda.synchronize()
+        U.assert_close(U.to_host_bits(c), ref, f"untuned {op}")
+        for mode in LAYOUTS:
+            B.axonn_linear_tuned_set(op, M, N, K, mode)
+            assert B.axonn_linear_tuned(op, M, N, K)["best_layout_all_in"] == B.LAYOUTS[mode]
+            for held in (b_t, None):
+                c.view(torch.int16).fill_(0x7FC0)
+                used = B.axonn_linear_tuned_call(op, M, N, K, a, b, c, held, scratch)
+                torch.cuda.synchronize()
+                assert used == B.LAYOUTS[mode], (op, mode, used)
+                U.assert_close(U.to_host_bits(c), ref, f"tuned {op} in {mode}, held copy {held is not None}")
+            # no room to re-store: the natural mode runs, unless the held copy is all that mode needs
+            c.view(torch.int16).fill_(0x7FC0)
+            used = B.axonn_linear_tuned_call(op, M, N, K, a, b, c, b_t, None)
+            torch.cuda.synchronize()
+            needs_first = (mode == "TN") != (nat == "TN")
+            assert used == (B.LAYOUTS[nat] if needs_first else B.LAYOUTS[mode])
+            U.assert_close(U.to_host_bits(c), ref, f"tuned {op} in {mode}, no scratch")
+        assert np.array_equal(U.to_host_bits(a), A) and np.array_equal(U.to_host_bits(b), Bm)   # operands untouched
+    finally:
+        B.axonn_linear_tune_reset()
