@@ -61,8 +61,16 @@ def summarize(d: str, out=sys.stdout):
         v = dur[k]
         print(f"{k:<22s} calls {len(v):5d}  mean {sum(v) / len(v) / 1e3:9.2f} us  min {min(v) / 1e3:9.2f}  "
               f"max {max(v) / 1e3:9.2f}  total {sum(v) / 1e6:9.3f} ms", file=out)
-        for c, vals in sorted(ctr.get(k, {}).items()):
-            print(f"    {c:<28s} mean per dispatch {sum(vals) / len(vals):.6g}  (n={len(vals)})", file=out)
+        means = {c: sum(vals) / len(vals) for c, vals in ctr.get(k, {}).items()}
+        for c in sorted(means):
+            print(f"    {c:<28s} mean per dispatch {means[c]:.6g}  (n={len(ctr[k][c])})", file=out)
+        # derived: GRBM_GUI_ACTIVE is summed over the 8 XCDs, SQ_VALU_MFMA_BUSY_CYCLES over 256 CUs x 4 SIMDs
+        if "SQ_VALU_MFMA_BUSY_CYCLES" in means and means.get("GRBM_GUI_ACTIVE"):
+            print(f"    -> MFMA busy {means['SQ_VALU_MFMA_BUSY_CYCLES'] / 1024.0 / (means['GRBM_GUI_ACTIVE'] / 8.0) * 100:.1f} % of "
+                  f"the kernel's cycles", file=out)
+        if "SQ_LDS_BANK_CONFLICT" in means and means.get("SQ_LDS_IDX_ACTIVE"):
+            print(f"    -> LDS bank-conflict cycles / LDS-active cycles {means['SQ_LDS_BANK_CONFLICT'] / means['SQ_LDS_IDX_ACTIVE'] * 100:.1f} %",
+                  file=out)
     return dur, ctr
 
 
