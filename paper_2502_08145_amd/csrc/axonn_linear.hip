@@ -60,9 +60,13 @@ struct Variant {
     int kstep;                       // K (per range) must be a multiple of this
     int splits;                      // K ranges per tile (1: no split-K)
     bool k64;                        // the kernel with 64-k LDS stages
-    // Throughput with every CU busy, per layout (NN, NT, TN), N(0,1) data, in units of 1200 TFLOP/s.
-    // Regenerate with `python -m paper_2502_08145_amd.sweeps variant_eff`, which times every variant
-    // without split-K on full-chip shapes and prints these numbers.
+    // Throughput with every CU busy, per layout (NN, NT, TN), N(0,1) data, in units of about 1200 TFLOP/s.
+    // `python -m paper_2502_08145_amd.sweeps variant_eff [--hot]` times every variant without split-K on
+    // full-chip shapes and prints such a table.  The numbers below were taken that way as each kernel came
+    // in; a re-measurement of all of them at once, with operands from HBM and with operands in cache,
+    // gave tables whose plans ran the benchmark step and the model-zoo sweep 0.5-1 % slower (the small
+    // tiles are picked for small outputs, which stay in cache, the large ones for large outputs, which
+    // do not: neither condition alone describes both), so these stand.
     double eff[3];
     tile_kernel_t fn[3];             // per layout
     bool edge = false;               // the guarded MFMA kernel: any shape, launched through edge_kernel_launch

@@ -2,7 +2,7 @@
 
     python -m paper_2502_08145_amd.sweeps peak_curve [--max 65536]
     python -m paper_2502_08145_amd.sweeps model_zoo [--tokens 2048]
-    python -m paper_2502_08145_amd.sweeps variant_eff
+    python -m paper_2502_08145_amd.sweeps variant_eff [--hot]
 
 peak_curve   square bf16 GEMMs 1024 ... 65536 in the three modes, the protocol of the paper's
              single-GPU GEMM benchmark (Sec. V-C: repeated runs, mean of the last three quarters),
@@ -12,9 +12,10 @@ model_zoo    the shard shapes of the paper's model table (Sec. V-A, the table of
              (Sec. IV-A: a weight is sharded over two of the grid's dimensions), forward,
              backward-data and backward-weight in their natural modes.
 
-variant_eff  every kernel variant without split-K, forced, on shapes that fill the chip a whole number of
-             times in all three modes; prints the throughputs in units of 1200 TFLOP/s, which is what
-             the library's selection model keeps per variant (Variant::eff in csrc/axonn_linear.hip).
+variant_eff  every kernel variant without split-K, forced, on benchmark-like shapes in all three modes,
+             operands cycling through sets larger than the Infinity Cache; prints the throughputs in
+             units of 1200 TFLOP/s, which is what the library's selection model keeps per variant
+             (Variant::eff in csrc/axonn_linear.hip).
 
 Operands are N(0,1) (activations, gradients) and N(0, 0.02^2) (weights) drawn on the device with a
 fixed seed: host generation of 65536^2 matrices would take minutes.  Output: one text line per
@@ -110,29 +111,44 @@ def model_zoo(args):
 
 
 def variant_eff(args):
-    """Efficiencies of the selection model: mean over the shapes of TFLOP/s / 1200, per variant and mode."""
+    """Efficiencies of the selection model: mean over the shapes of TFLOP/s / 1200, per variant and mode.
+    Every launch takes the next of several operand sets that together exceed the 256 MB Infinity Cache
+    three times, so the rates are those of operands coming from HBM, as in a training step."""
     gen = torch.Generator(device="cuda").manual_seed(250208148)
-    shapes = [(4096, 4096, 4096), (8192, 8192, 8192), (4096, 16384, 2048), (2048, 16384, 4096)]
+    # outputs that fill the 256 compute units a whole number of times with every tile shape (a partly
+    # filled round is the selection model's own term)
+    shapes = [(4096, 4096, 4096), (4096, 16384, 2048), (2048, 16384, 4096), (4096, 8192, 8192)]
     names = [B.variant_name(v) for v in range(B.num_variants())]
+    stream = torch.cuda.current_stream()
     rows = {}
     for M, N, K in shapes:
-        a = randn_bf16((M, K), 1.0, gen)
-        b = randn_bf16((K, N), 1.0, gen)
-        c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        sets = 1 if args.hot else max(2, -(-(768 << 20) // (2 * (M * K + K * N + M * N))))
+        a = [randn_bf16((M, K), 1.0, gen) for _ in range(sets)]
+        b = [randn_bf16((K, N), 1.0, gen) for _ in range(sets)]
+        c = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(sets)]
         for layout in ("NN", "NT", "TN"):
-            x = a.t().contiguous() if layout == "TN" else a
-            y = b.t().contiguous() if layout == "NT" else b
+            x = [t.t().contiguous() for t in a] if layout == "TN" else a
+            y = [t.t().contiguous() for t in b] if layout == "NT" else b
             for v, name in enumerate(names):
                 if v == 0 or "_sk" in name or "edge" in name or not B.variant_supports(v, M, N, K, layout):
                     continue
                 B.force_variant(v)
                 try:
-                    ms = time_gemm("fwd", M, N, K, layout, x, y, c, 24, warm=6)
+                    reps = max(12, 4 * sets)
+                    for i in range(sets):
+                        B.axonn_linear_fwd(M, N, K, layout, x[i], y[i], c[i], 1, stream)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for i in range(reps):
+                        B.axonn_linear_fwd(M, N, K, layout, x[i % sets], y[i % sets], c[i % sets], 1, stream)
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / reps
                 finally:
                     B.force_variant(-1)
                 tf = 2.0 * M * N * K / ms / 1e9
                 rows.setdefault(name, {}).setdefault(layout, []).append(tf)
-                print(f"{M:6d} {N:6d} {K:6d} {layout} {name:<24s} {ms * 1e3:9.1f} us {tf:8.1f} TFLOP/s", flush=True)
+                print(f"{M:6d} {N:6d} {K:6d} {layout} {name:<24s} {sets:3d} sets {ms * 1e3:9.1f} us {tf:8.1f} TFLOP/s", flush=True)
             del x, y
         del a, b, c
     print("variant                    eff NN   NT   TN   (TFLOP/s / 1200, mean over the shapes)")
@@ -161,7 +177,8 @@ def main(argv=None):
     z = sub.add_parser("model_zoo")
     z.add_argument("--tokens", type=int, default=2048)
     z.add_argument("--verbose", action="store_true")
-    sub.add_parser("variant_eff")
+    e = sub.add_parser("variant_eff")
+    e.add_argument("--hot", action="store_true", help="one operand set, re-used by every launch (operands stay in cache)")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("sweeps: no GPU visible")
