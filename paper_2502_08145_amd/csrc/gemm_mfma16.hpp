@@ -80,6 +80,9 @@ struct LoadPlan16 {
 template <int BM, int BN, int MI, int NI>
 __device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const SplitK& sk, int krange, int tile_id,
                                                    int tiles, int wave, int lane, int t) {
+    // the lane number through an opaque move: what is derived from it here is then computed here, after
+    // the K loop, instead of being hoisted above it and kept (or spilled) across it
+    asm volatile("" : "+v"(lane));
     const size_t in_slot = (size_t)wave * (MI * NI * 64) + lane;
     if (krange != 0) {
         const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
@@ -140,6 +143,7 @@ __device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const S
 // K = 2048 (the stores start eight times earlier).
 template <int TM, int TN, int MI, int NI>
 __device__ __forceinline__ void store_tile16(f32x4 (&acc)[MI][NI], uint8_t* smem, uint16_t* pc, int ldc, int wave, int lane) {
+    asm volatile("" : "+v"(lane));   // see split_k_exchange16: keeps the epilogue's addresses out of the K loop's registers
     constexpr int CPR = TN / 8;   // 16-byte chunks per row of the wave tile (8 or 16)
     constexpr uint32_t CMASK = CPR - 1;
     const uint32_t quad = lane >> 4, r16 = lane & 15;
