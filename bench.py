@@ -124,6 +124,11 @@ def main():
                          "steps touch 768 MiB between them (1 for the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-power-sample", action="store_true", help="skip the amd-smi reading of power and clock")
+    ap.add_argument("--event-every", type=int, default=4, metavar="E",
+                    help="bracket the dominant kernel's launches with events in every E-th step of the timed region")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a captured HIP graph (small products: no launch gaps from Python); "
+                         "reported beside the eager figure, which stays `value`")
     ap.add_argument("--tune", action="store_true",
                     help="after the timed region, run the mode tuner on every GEMM of the workload and log its table")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
@@ -243,15 +248,18 @@ def main():
     is_dom = [("+" not in g["variant"]) and f"{g['variant']}/{g['layout']}" == dom for g in gemms]
 
     # ---- timed region: K steps.  HIP events on the launch stream bracket only the launches of the dominant
-    # kernel (an event record costs about 3 us of stream time on this part: with one after every GEMM, as in
-    # the pass above, the step is 3-5 % longer).
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) if d else None for d in is_dom]
-          for _ in range(args.steps)]
+    # kernel, and only in every `--event-every`-th step: an event record costs 3-6 us of stream time on this
+    # part (the next kernel waits for the record's barrier packet), so one after every GEMM, as in the pass
+    # above, makes the step 3-5 % longer, and a pair around three launches of every step still 1 %.
+    every = max(1, args.event_every)
+    probed = [s % every == 0 for s in range(args.steps)]
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) if (d and probed[s]) else None for d in is_dom]
+          for s in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
         for gi, g in enumerate(gemms):
-            if is_dom[gi]:
+            if ev[s][gi] is not None:
                 ev[s][gi][0].record(stream)
                 launch(g, s % sets)
                 ev[s][gi][1].record(stream)
@@ -264,11 +272,11 @@ def main():
     for g in gemms:
         if not all(torch.isfinite(c.float()).all() for c in g["c"]):
             sys.exit(f"bench.py: non-finite output in {g['name']}")
-    timed = [float(np.mean([ev[s][gi][0].elapsed_time(ev[s][gi][1]) for s in range(args.steps)])) if is_dom[gi] else None
+    timed = [float(np.mean([ev[s][gi][0].elapsed_time(ev[s][gi][1]) for s in range(args.steps) if probed[s]])) if is_dom[gi] else None
              for gi in range(len(gemms))]
     groups = groups_of(timed)
     achieved = groups[dom]["flops"] / groups[dom]["ms"] / 1e9
-    log(f"timed region: {ms_per_step * 1e3:.1f} us per step; dominant kernel {dom}: {groups[dom]['n']} launches per step, "
+    log(f"timed region: {ms_per_step * 1e3:.1f} us per step; dominant kernel {dom} (events in {sum(probed)} of {args.steps} steps): {groups[dom]['n']} launches per step, "
         f"mean {groups[dom]['ms'] / groups[dom]['n'] * 1e3:.1f} us ({achieved:.1f} TFLOP/s)")
     # HBM bytes per launch of that kernel from the stored rocprofv3 counter runs -- only if they were
     # taken with the kernel sources this run uses (else null: a stale reading is worse than none)
@@ -290,6 +298,29 @@ def main():
                 "launches_per_step": groups[dom]["n"],
                 "mean_launch_us": round(groups[dom]["ms"] / groups[dom]["n"] * 1e3, 2),
                 "flops_per_launch": groups[dom]["flops"] / groups[dom]["n"]}
+
+    # ---- the same step replayed from a HIP graph: one graph holds a step on every operand set in turn ----
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(stream)
+        with torch.cuda.graph(graph, stream=side):
+            cs = torch.cuda.current_stream()
+            for r in range(sets):
+                for g in gemms:
+                    B.OPS[g["op"]](g["M"], g["N"], g["K"], g["layout"], g["a"][r], g["b"][r], g["c"][r], 1, cs)
+        reps = max(1, args.steps // sets)
+        for _ in range(max(1, args.warmup // sets)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / (reps * sets)
+        log(f"step replayed from a HIP graph: {graph_ms * 1e3:.1f} us ({step_flops / graph_ms / 1e9:.1f} TFLOP/s); "
+            f"launched eagerly from Python: {ms_per_step * 1e3:.1f} us ({value:.1f} TFLOP/s)")
 
     # ---- context: board power and shader clock while the step runs (the published peak assumes 2.4 GHz) ----
     board = None
@@ -413,6 +444,7 @@ def main():
                       "step_tflop": round(step_flops / 1e12, 4), "operand_sets": sets},
            "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
            "board": board,
+           "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 

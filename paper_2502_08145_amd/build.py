@@ -39,7 +39,7 @@ def source_id() -> str:
     taken with, so that a stored counter reading can be told from one of an older kernel."""
     import hashlib
     h = hashlib.sha256()
-    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC))
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp", ".h")))
     files.append(os.path.join(os.path.dirname(HERE), "include", "axonn_linear.h"))
     for f in files:
         h.update(os.path.basename(f).encode())
