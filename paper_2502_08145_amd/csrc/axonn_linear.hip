@@ -87,8 +87,8 @@ static std::vector<Variant> make_variants() {
         v.push_back(x);
     };
     auto k64 = [&](const char* name, int splits) {
-        Variant x{name, 256, 256, 512, TileCfgK64::LDS_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
-                  {1.17, 1.13, 1.15}, {nullptr, nullptr, nullptr}};
+        Variant x{name, 256, 256, 512, TileCfgK64::LDS3_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
+                  {1.17, 1.17, 1.15}, {nullptr, nullptr, nullptr}};
         for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel(splits > 1, l);
         v.push_back(x);
     };
@@ -235,14 +235,12 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     constexpr double kFixedK = 128.0;
     const Variant& var = variants()[v];
     if (!variant_supports(v, M, N, K, layout) || (var.splits > 1 && !allow_split) || var.eff[layout] <= 0.0) return -1.0;
-    // The 64-k kernels hold two K-steps less in LDS than the 32-k ring; over very long K ranges the
-    // workgroups behind one L2 drift further apart than that tolerates.  Measured with the final
-    // epilogue: in NT the 64-k kernel is 4-5 % behind the ring at K = 32768 and 49152 (8192 x 8192
-    // outputs) and ahead of it up to 24576; in NN and TN it stays 1-5 % ahead at those K.  The split-K
-    // forms were compared up to K = 32768 only.
-    if (var.k64) {
-        if (var.splits == 1 ? (layout == AXONN_NT && K > 24576) : K > 32768) return -1.0;
-    }
+    // Long K: without split-K the 64-k kernels lead the 32-k ring in every mode (8192 x 8192 x 32768 and
+    // x 49152: NN and TN by 1-5 %, NT, since its A panel is triple-buffered, by 9-10 %).  With split-K
+    // they lead in NN and NT at any K tried (2048 x 2048 x 65536 in four ranges: +5 % and +11 %;
+    // 1024 x 2048 x 131072 in eight: +3 % and +13 %), in TN the ring is level or up to 8 % ahead above
+    // K = 32768.
+    if (var.k64 && var.splits > 1 && layout == AXONN_TN && K > 32768) return -1.0;
     // The resident-workgroup form of the 64-k kernel: measured against one workgroup per tile in the
     // benchmark's sequence, 1.3-1.9 % less time for the TN products of three and four tiles per compute
     // unit, +-1 % for NN, 1.6 % MORE for NT with two tiles and 2.5 % more with a single tile.

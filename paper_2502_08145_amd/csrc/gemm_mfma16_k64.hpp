@@ -16,7 +16,14 @@
 //    of iteration i+1 (other buffer), and the direct loads of iteration i+2 go out into the buffer
 //    that iteration i has just finished with.  At the barrier every load issued so far must have
 //    landed (vmcnt(0)): those of iteration i+1, issued one iteration earlier, i.e. a lead of
-//    almost two sub-steps.
+//    almost two sub-steps;
+//  * optionally (SCHED 1 or 2) one operand gets a THIRD buffer (160 KB in all) and its loads move to
+//    sub-step 0: the buffer they go to was released at the previous iteration's barrier, they have
+//    three sub-steps to land, and the load path (which delivers some 52 bytes a clock per compute
+//    unit, so the 64 KB of an iteration keep it busy for most of one sub-step) carries half an
+//    iteration's bytes in either sub-step instead of all of them in one.  At the barrier the loads
+//    that sub-step 0 has just issued may still be in flight (vmcnt(QL): loads complete in order).
+//    Which modes gain from it is a measurement (see kernels_k64.hip).
 //
 // Measured: with eight waves it is the fastest kernel in all three modes (NN and NT: 3-4 % over the
 // 32-k kernel in the benchmark step, more for the split-K forms; TN: 2-4 % since C is streamed out as
@@ -35,6 +42,8 @@ struct TileCfgK64 {
     static constexpr int KS = 64;                                  // k per LDS buffer
     static constexpr int A_BYTES = BM * KS * 2, BUF_BYTES = (BM + BN) * KS * 2;
     static constexpr int LDS_BYTES = 2 * BUF_BYTES;                // 128 KB; the epilogue needs BM*BN*2 = 128 KB
+    static constexpr int B_BYTES = BN * KS * 2;
+    static constexpr int LDS3_BYTES = LDS_BYTES + A_BYTES;         // 160 KB: with a third buffer for one operand
     static constexpr int MIN_K = 2 * KS;                           // the prologue fills both buffers
 };
 
@@ -142,7 +151,7 @@ struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32
 };
 
 // Requires M % 256 == 0, N % 256 == 0, K % 64 == 0, K >= 128 (per K range when split).
-template <int WN, bool A_KC, bool B_KC, bool SPLITK>
+template <int WN, bool A_KC, bool B_KC, bool SPLITK, int SCHED>
 __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n, int group_m, SplitK sk) {
@@ -150,7 +159,11 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     static_assert(WN == 2 || WN == 4, "2 x 2 or 2 x 4 waves");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, NW = 2 * WN;
     constexpr int TM = BM / 2, TN = BN / WN, MI = TM / 16, NI = TN / 16, NM = MI * NI;
-    constexpr uint32_t BUF = Cfg::BUF_BYTES, REGION_B = Cfg::A_BYTES;
+    // SCHED 0: two buffers per operand, all loads of an iteration in sub-step 1; 1: three A buffers, A's
+    // loads in sub-step 0; 2: three B buffers, B's loads in sub-step 0
+    static_assert(SCHED >= 0 && SCHED <= 2, "load schedule");
+    constexpr int NAB = SCHED == 1 ? 3 : 2;
+    constexpr uint32_t ABUF = Cfg::A_BYTES, BBUF = Cfg::B_BYTES, REGION_B = NAB * Cfg::A_BYTES;
     constexpr int QL = 32 / NW;   // direct loads per wave, operand and iteration
     constexpr int NLD = 2 * QL, NRD = MI + NI;   // ... and loads / fragment reads per wave and iteration / sub-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -175,18 +188,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     OpB opb;
     opa.init(A + (A_KC ? k0 : k0 * lda), m0, 2u * (uint32_t)lda, lane, wave, lds0, wm * TM);
     opb.init(B + (B_KC ? k0 : k0 * ldb), n0, 2u * (uint32_t)ldb, lane, wave, lds0, wn * TN);
-    // load number X of an iteration (0..7: A, 8..15: B) into the buffer at `buf`
-    auto issue = [&](auto x_c, uint32_t buf) __attribute__((always_inline)) {
-        constexpr int X = decltype(x_c)::value;
-        if constexpr (X < QL)
-            opa.template issue<X>(buf);
-        else
-            opb.template issue<X - QL>(buf);
-    };
-    auto advance_window = [&]() __attribute__((always_inline)) {
-        opa.advance();
-        opb.advance();
-    };
+    // load number X (0 .. QL-1) of an operand's panel of one iteration into the buffer at `buf`
+    auto issue_a = [&](auto x_c, uint32_t buf) __attribute__((always_inline)) { opa.template issue<decltype(x_c)::value>(buf); };
+    auto issue_b = [&](auto x_c, uint32_t buf) __attribute__((always_inline)) { opb.template issue<decltype(x_c)::value>(buf); };
 
     f32x4 acc[MI][NI];
 #pragma unroll
@@ -237,42 +241,70 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
                 opb.template read<X - MI>(fb[S][X - MI], cb);
         });
     };
-    auto load_cluster = [&](auto q_c, uint32_t buf) __attribute__((always_inline)) {
-        constexpr int Q = decltype(q_c)::value;
-        constexpr int LF = Q * NLD / NC, LL = (Q + 1) * NLD / NC;
-        static_for<LL - LF>([&](auto d) __attribute__((always_inline)) { issue(Int<LF + decltype(d)::value>{}, buf); });
+    // cluster Q's share of the loads that go out in sub-step S: with SCHED 0 all 2*QL of an iteration
+    // in sub-step 1 (A's first), else the QL of the triple-buffered operand in sub-step 0 and the QL of
+    // the other one in sub-step 1
+    auto load_cluster = [&](auto q_c, auto s_c, uint32_t abuf, uint32_t bbuf) __attribute__((always_inline)) {
+        constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
+        if constexpr (SCHED == 0) {
+            constexpr int LF = Q * NLD / NC, LL = (Q + 1) * NLD / NC;
+            static_for<LL - LF>([&](auto d) __attribute__((always_inline)) {
+                constexpr int X = LF + decltype(d)::value;
+                if constexpr (X < QL)
+                    issue_a(Int<X>{}, abuf);
+                else
+                    issue_b(Int<X - QL>{}, bbuf);
+            });
+        } else {
+            constexpr int LF = Q * QL / NC, LL = (Q + 1) * QL / NC;
+            static_for<LL - LF>([&](auto d) __attribute__((always_inline)) {
+                if constexpr ((S == 0) == (SCHED == 1))
+                    issue_a(Int<LF + decltype(d)::value>{}, abuf);
+                else
+                    issue_b(Int<LF + decltype(d)::value>{}, bbuf);
+            });
+        }
     };
 
-    // ---- prologue: iterations 0 and 1 into buffers 0 and 1 -----------------------------------------
-    static_for<NLD>([&](auto x) __attribute__((always_inline)) { issue(x, 0u); });
-    advance_window();
-    static_for<NLD>([&](auto x) __attribute__((always_inline)) { issue(x, BUF); });
-    advance_window();
+    // ---- prologue: iterations 0 and 1 into the first two buffers of each operand ---------------------
+    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_a(x, 0u); });
+    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_b(x, 0u); });
+    opa.advance();
+    opb.advance();
+    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_a(x, ABUF); });
+    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_b(x, BBUF); });
+    opa.advance();
+    opb.advance();
     wait_vmcnt<NLD>();   // iteration 0 has landed
     __builtin_amdgcn_s_barrier();
     AXONN_FENCE();
 
-    // `cur`: byte offset of the buffer of the running iteration
-    uint32_t cur = 0;
+    // byte offsets of the A buffers of the running iteration, the next one and the one after, and of
+    // the running iteration's B buffer (the other one is the next iteration's)
+    uint32_t a0 = 0, a1 = ABUF, a2 = SCHED == 1 ? 2 * ABUF : 0, b0 = 0, b1 = BBUF, b2 = SCHED == 2 ? 2 * BBUF : 0;
     // One sub-step S of the running iteration.
-    //   READ: fragments for the following sub-step are read (S = 0: sub-step 1 of the same buffer;
-    //         S = 1: sub-step 0 of the other buffer, after the barrier).
-    //   LOAD (S = 1): the iteration after next is fetched into the running buffer, after the barrier.
+    //   READ: fragments for the following sub-step are read (S = 0: sub-step 1 of the same buffers;
+    //         S = 1: sub-step 0 of the next iteration's buffers, after the barrier).
+    //   LOAD: the panels of the iteration after next are fetched, A's in sub-step 0 into the third A
+    //         buffer (free since the previous iteration's barrier), B's in sub-step 1, after the barrier,
+    //         into the running B buffer: the load path carries the same number of bytes in either sub-step.
     auto substep = [&](auto s_c, auto read_c, auto load_c, auto phase_c) __attribute__((always_inline)) {
         constexpr int S = decltype(s_c)::value;
         constexpr int P0 = PB + (decltype(phase_c)::value ? NM / 8 : 0);   // MFMAs before the first cluster
         constexpr int R = 3 * NM / 4 - P0;
         constexpr bool READ = decltype(read_c)::value, LOAD = decltype(load_c)::value;
-        static_assert(!LOAD || (S == 1 && READ), "loads go out in sub-step 1 of an iteration that has a successor");
+        static_assert(!LOAD || READ, "loads go out in iterations that have a successor");
         wait_fragments(s_c);
         AXONN_FENCE();
         mfma_range(s_c, Int<0>{}, Int<PB>{});
         AXONN_FENCE();
-        typename OpA::Cursor ca = opa.template cursor<1 - S>(S == 1 ? cur ^ BUF : cur);
-        typename OpB::Cursor cb = opb.template cursor<1 - S>(S == 1 ? cur ^ BUF : cur);
+        typename OpA::Cursor ca = opa.template cursor<1 - S>(S == 1 ? a1 : a0);
+        typename OpB::Cursor cb = opb.template cursor<1 - S>(S == 1 ? b1 : b0);
         if constexpr (READ && S == 1) {
-            wait_vmcnt<0>();                 // the next iteration's panels: every load of this wave ...
-            __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffer is free
+            // the next iteration's panels have landed: every load of this wave but the A loads that
+            // sub-step 0 has just issued (loads complete in order) ...
+            wait_vmcnt<(LOAD && SCHED != 0) ? QL : 0>();
+            __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffers are free
             AXONN_FENCE();
         }
         if constexpr (P0 > PB) {
@@ -282,7 +314,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         static_for<NC>([&](auto q_c) __attribute__((always_inline)) {
             constexpr int Q = decltype(q_c)::value;
             if constexpr (READ) read_cluster(q_c, Int<1 - S>{}, ca, cb);
-            if constexpr (LOAD) load_cluster(q_c, cur);
+            if constexpr (LOAD && (S == 1 || SCHED != 0)) load_cluster(q_c, s_c, SCHED == 1 ? a2 : a0, SCHED == 2 ? b2 : b0);
             AXONN_FENCE();
             if constexpr (Q < NC - 1)
                 mfma_range(s_c, Int<P0 + Q * R / (NC - 1)>{}, Int<P0 + (Q + 1) * R / (NC - 1)>{});
@@ -290,8 +322,28 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
                 mfma_range(s_c, Int<P0 + R>{}, Int<NM>{});
             AXONN_FENCE();
         });
-        if constexpr (LOAD) advance_window();
-        if constexpr (S == 1) cur ^= BUF;
+        if constexpr (LOAD) {
+            if constexpr (SCHED == 0 ? S == 1 : (S == 0) == (SCHED == 1)) opa.advance();
+            if constexpr (SCHED == 0 ? S == 1 : (S == 0) == (SCHED == 2)) opb.advance();
+        }
+        if constexpr (S == 1) {
+            // the buffers move up: the one the loads have just gone to (SCHED 0: the running one) comes last
+            const uint32_t a = a0, b = b0;
+            a0 = a1;
+            b0 = b1;
+            if constexpr (SCHED == 1) {
+                a1 = a2;
+                a2 = a;
+            } else {
+                a1 = a;
+            }
+            if constexpr (SCHED == 2) {
+                b1 = b2;
+                b2 = b;
+            } else {
+                b1 = b;
+            }
+        }
     };
     using Yes = std::true_type;
     using No = std::false_type;
@@ -312,7 +364,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
             static_for<NC>([&](auto q_c) __attribute__((always_inline)) { read_cluster(q_c, Int<0>{}, ca, cb); });
         }
         for (int it = KI - 2; it > 0; --it) {
-            substep(Int<0>{}, Yes{}, No{}, phase_c);
+            substep(Int<0>{}, Yes{}, Yes{}, phase_c);
             substep(Int<1>{}, Yes{}, Yes{}, phase_c);
         }
         substep(Int<0>{}, Yes{}, No{}, phase_c);   // iteration KI-2: nothing left to fetch
@@ -323,7 +375,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         } else {
             wait_fragments(Int<1>{});
             AXONN_FENCE();
-            uint8_t* const epi = smem + (cur ^ BUF) + wave * (16 * TN * 2);
+            uint8_t* const epi = smem + (SCHED == 1 ? a2 : a1) + wave * (16 * TN * 2);   // an A buffer of an earlier iteration
             uint16_t* const pc = C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN;
             static_for<MI>([&](auto i_c) __attribute__((always_inline)) {
                 constexpr int I = decltype(i_c)::value;
