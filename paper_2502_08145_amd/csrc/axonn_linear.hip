@@ -112,6 +112,15 @@ static std::vector<Variant> make_variants() {
         x.resident = TileCfgK64P::MAX_WORKGROUPS;
         v.push_back(x);
     }
+    // half tiles with 64-k stages: NT only (eff from 2048 x 4096 x 4096 and 4096^3 against the ring's half tiles)
+    auto k64h = [&](const char* name, int bm, int bn, double nt) {
+        Variant x{name, bm, bn, 256, k64_lds_bytes(bm, bn, 3), TileCfgK64::MIN_K, TileCfgK64::KS, 1, true,
+                  {0.0, nt, 0.0}, {nullptr, nullptr, nullptr}};
+        for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel_half(bm, bn, l);
+        v.push_back(x);
+    };
+    k64h("mfma16k64_256x128", 256, 128, 0.95);
+    k64h("mfma16k64_128x256", 128, 256, 0.94);
     static const char* const k64_sk[] = {"mfma16k64_256x256_w8_sk2", "mfma16k64_256x256_w8_sk3", "mfma16k64_256x256_w8_sk4", "mfma16k64_256x256_w8_sk5",
                                          "mfma16k64_256x256_w8_sk6", "mfma16k64_256x256_w8_sk7", "mfma16k64_256x256_w8_sk8"};
     for (int sp = 2; sp <= 8; ++sp) k64(k64_sk[sp - 2], sp);

@@ -52,9 +52,9 @@ struct TileCfgK64 {
 //   advance()            window one iteration (64 k) on
 //   cursor(S, buf)       read addresses for sub-step S of that buffer
 //   read<I>(frag, cur)   fragment of 16-row block I
-template <int REGION, int NW>
+template <int ROWS, int REGION, int NW>
 struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks swizzled by (row>>1)&7
-    static constexpr int QL = 32 / NW;   // loads per wave and iteration: row groups QL*wave .. (8 rows each)
+    static constexpr int QL = ROWS / 8 / NW;   // loads per wave and iteration: row groups QL*wave .. (8 rows each)
     using Frag = Frag128;
     struct Cursor {
         uint32_t a;
@@ -108,14 +108,14 @@ struct OperandK64KContig {   // global P[row * ld + k]; LDS [row][64 k], chunks 
     }
 };
 
-template <int REGION, int NW, int NB>
+template <int ROWS, int REGION, int NW, int NB>
 struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32-k stages of OperandMNContig
-    using Inner = OperandMNContig<256, REGION, NW, NB>;
+    using Inner = OperandMNContig<ROWS, REGION, NW, NB>;
     static constexpr int QH = Inner::QL;   // loads per wave and 32-k stage
     static constexpr int QL = 2 * QH;
     using Frag = typename Inner::Frag;
     using Cursor = typename Inner::Cursor16;
-    static constexpr uint32_t HALF = 256 * KB * 2;   // bytes of one 32-k stage
+    static constexpr uint32_t HALF = ROWS * KB * 2;   // bytes of one 32-k stage
     Inner in;
     uint32_t voff_hi[QH];     // the loads of the second stage: 32 k-rows on
 
@@ -150,22 +150,34 @@ struct OperandK64MNContig {   // global P[k * ld + row]; the buffer holds two 32
     }
 };
 
-// Requires M % 256 == 0, N % 256 == 0, K % 64 == 0, K >= 128 (per K range when split).
-template <int WN, bool A_KC, bool B_KC, bool SPLITK, int SCHED>
+// Load schedules of gemm_tile_kernel_k64 (SCHED):
+//   0  two buffers per operand; all loads of an iteration in sub-step 1, into the running buffers
+//   1  three A buffers, A's loads in sub-step 0; B as in 0
+//   2  three B buffers, B's loads in sub-step 0; A as in 0
+//   3  three buffers each (fits for the 128 x 256 and 256 x 128 tiles); half of an iteration's loads in
+//      either sub-step
+constexpr int k64_a_buffers(int sched) { return (sched == 1 || sched == 3) ? 3 : 2; }
+constexpr int k64_b_buffers(int sched) { return (sched == 2 || sched == 3) ? 3 : 2; }
+constexpr int k64_lds_bytes(int bm, int bn, int sched) {
+    const int ring = (k64_a_buffers(sched) * bm + k64_b_buffers(sched) * bn) * TileCfgK64::KS * 2, epi = bm * bn * 2;
+    return ring > epi ? ring : epi;
+}
+
+// Requires M % BM == 0, N % BN == 0, K % 64 == 0, K >= 128 (per K range when split).
+template <int BM, int BN, int WN, bool A_KC, bool B_KC, bool SPLITK, int SCHED>
 __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
     int K, int lda, int ldb, int ldc, int tiles_m, int tiles_n, int group_m, SplitK sk) {
     using Cfg = TileCfgK64;
     static_assert(WN == 2 || WN == 4, "2 x 2 or 2 x 4 waves");
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, NW = 2 * WN;
+    static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256), "tile extents are 128 or 256");
+    constexpr int NW = 2 * WN;
     constexpr int TM = BM / 2, TN = BN / WN, MI = TM / 16, NI = TN / 16, NM = MI * NI;
-    // SCHED 0: two buffers per operand, all loads of an iteration in sub-step 1; 1: three A buffers, A's
-    // loads in sub-step 0; 2: three B buffers, B's loads in sub-step 0
-    static_assert(SCHED >= 0 && SCHED <= 2, "load schedule");
-    constexpr int NAB = SCHED == 1 ? 3 : 2;
-    constexpr uint32_t ABUF = Cfg::A_BYTES, BBUF = Cfg::B_BYTES, REGION_B = NAB * Cfg::A_BYTES;
-    constexpr int QL = 32 / NW;   // direct loads per wave, operand and iteration
-    constexpr int NLD = 2 * QL, NRD = MI + NI;   // ... and loads / fragment reads per wave and iteration / sub-step
+    static_assert(SCHED >= 0 && SCHED <= 3, "load schedule");
+    constexpr int NAB = k64_a_buffers(SCHED), NBB = k64_b_buffers(SCHED);
+    constexpr uint32_t ABUF = BM * Cfg::KS * 2, BBUF = BN * Cfg::KS * 2, REGION_B = NAB * ABUF;
+    static_assert(k64_lds_bytes(BM, BN, SCHED) <= 160 * 1024, "LDS per workgroup");
+    constexpr int NRD = MI + NI;   // fragment reads per wave and sub-step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int t = threadIdx.x;
@@ -174,15 +186,16 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- workgroup -> output tile and K range ------------------------------------------------
-    const TileWork work = map_workgroup<SPLITK, true>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
+    const TileWork work = map_workgroup<SPLITK, BM * BN == 256 * 256>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
     const int tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange, ktotal = work.ktotal;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int64_t k0 = (int64_t)krange * ktotal;
 
     // ---- operands ------------------------------------------------------------------------------------
-    using OpA = typename std::conditional<A_KC, OperandK64KContig<0, NW>, OperandK64MNContig<0, NW, MI / 2>>::type;
-    using OpB = typename std::conditional<B_KC, OperandK64KContig<REGION_B, NW>, OperandK64MNContig<REGION_B, NW, NI / 2>>::type;
-    static_assert(OpA::QL == QL && OpB::QL == QL, "loads per wave");
+    using OpA = typename std::conditional<A_KC, OperandK64KContig<BM, 0, NW>, OperandK64MNContig<BM, 0, NW, MI / 2>>::type;
+    using OpB = typename std::conditional<B_KC, OperandK64KContig<BN, REGION_B, NW>, OperandK64MNContig<BN, REGION_B, NW, NI / 2>>::type;
+    constexpr int QLA = OpA::QL, QLB = OpB::QL, NLD = QLA + QLB;   // direct loads per wave and iteration
+    static_assert(QLA == BM / 2 / NW / 4 && QLB == BN / 2 / NW / 4, "a load is 1 KB of a panel of BM (BN) x 64 bf16");
     const uint32_t lds0 = lds_address(smem);
     OpA opa;
     OpB opb;
@@ -241,38 +254,32 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
                 opb.template read<X - MI>(fb[S][X - MI], cb);
         });
     };
-    // cluster Q's share of the loads that go out in sub-step S: with SCHED 0 all 2*QL of an iteration
-    // in sub-step 1 (A's first), else the QL of the triple-buffered operand in sub-step 0 and the QL of
-    // the other one in sub-step 1
+    // cluster Q's share of the loads that go out in sub-step S.  The loads of an iteration are numbered
+    // A's first (0 .. QLA-1), then B's; sub-step S issues LS of them from number LO on.
     auto load_cluster = [&](auto q_c, auto s_c, uint32_t abuf, uint32_t bbuf) __attribute__((always_inline)) {
         constexpr int Q = decltype(q_c)::value, S = decltype(s_c)::value;
-        if constexpr (SCHED == 0) {
-            constexpr int LF = Q * NLD / NC, LL = (Q + 1) * NLD / NC;
-            static_for<LL - LF>([&](auto d) __attribute__((always_inline)) {
-                constexpr int X = LF + decltype(d)::value;
-                if constexpr (X < QL)
-                    issue_a(Int<X>{}, abuf);
-                else
-                    issue_b(Int<X - QL>{}, bbuf);
-            });
-        } else {
-            constexpr int LF = Q * QL / NC, LL = (Q + 1) * QL / NC;
-            static_for<LL - LF>([&](auto d) __attribute__((always_inline)) {
-                if constexpr ((S == 0) == (SCHED == 1))
-                    issue_a(Int<LF + decltype(d)::value>{}, abuf);
-                else
-                    issue_b(Int<LF + decltype(d)::value>{}, bbuf);
-            });
-        }
+        constexpr int LO = SCHED == 0 ? 0 : SCHED == 1 ? (S == 0 ? 0 : QLA) : SCHED == 2 ? (S == 0 ? QLA : 0) : (S == 0 ? 0 : NLD / 2);
+        constexpr int LS = SCHED == 0 ? (S == 0 ? 0 : NLD)
+                         : SCHED == 1 ? (S == 0 ? QLA : QLB)
+                         : SCHED == 2 ? (S == 0 ? QLB : QLA)
+                                      : (S == 0 ? NLD / 2 : NLD - NLD / 2);
+        constexpr int LF = LO + Q * LS / NC, LL = LO + (Q + 1) * LS / NC;
+        static_for<LL - LF>([&](auto d) __attribute__((always_inline)) {
+            constexpr int X = LF + decltype(d)::value;
+            if constexpr (X < QLA)
+                issue_a(Int<X>{}, abuf);
+            else
+                issue_b(Int<X - QLA>{}, bbuf);
+        });
     };
 
     // ---- prologue: iterations 0 and 1 into the first two buffers of each operand ---------------------
-    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_a(x, 0u); });
-    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_b(x, 0u); });
+    static_for<QLA>([&](auto x) __attribute__((always_inline)) { issue_a(x, 0u); });
+    static_for<QLB>([&](auto x) __attribute__((always_inline)) { issue_b(x, 0u); });
     opa.advance();
     opb.advance();
-    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_a(x, ABUF); });
-    static_for<QL>([&](auto x) __attribute__((always_inline)) { issue_b(x, BBUF); });
+    static_for<QLA>([&](auto x) __attribute__((always_inline)) { issue_a(x, ABUF); });
+    static_for<QLB>([&](auto x) __attribute__((always_inline)) { issue_b(x, BBUF); });
     opa.advance();
     opb.advance();
     wait_vmcnt<NLD>();   // iteration 0 has landed
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
 
     // byte offsets of the A buffers of the running iteration, the next one and the one after, and of
     // the running iteration's B buffer (the other one is the next iteration's)
-    uint32_t a0 = 0, a1 = ABUF, a2 = SCHED == 1 ? 2 * ABUF : 0, b0 = 0, b1 = BBUF, b2 = SCHED == 2 ? 2 * BBUF : 0;
+    uint32_t a0 = 0, a1 = ABUF, a2 = NAB == 3 ? 2 * ABUF : 0, b0 = 0, b1 = BBUF, b2 = NBB == 3 ? 2 * BBUF : 0;
     // One sub-step S of the running iteration.
     //   READ: fragments for the following sub-step are read (S = 0: sub-step 1 of the same buffers;
     //         S = 1: sub-step 0 of the next iteration's buffers, after the barrier).
@@ -303,7 +310,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         if constexpr (READ && S == 1) {
             // the next iteration's panels have landed: every load of this wave but the A loads that
             // sub-step 0 has just issued (loads complete in order) ...
-            wait_vmcnt<(LOAD && SCHED != 0) ? QL : 0>();
+            wait_vmcnt<!LOAD ? 0 : SCHED == 1 ? QLA : SCHED == 2 ? QLB : SCHED == 3 ? NLD / 2 : 0>();
             __builtin_amdgcn_s_barrier();    // ... and of the others; and the running buffers are free
             AXONN_FENCE();
         }
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         static_for<NC>([&](auto q_c) __attribute__((always_inline)) {
             constexpr int Q = decltype(q_c)::value;
             if constexpr (READ) read_cluster(q_c, Int<1 - S>{}, ca, cb);
-            if constexpr (LOAD && (S == 1 || SCHED != 0)) load_cluster(q_c, s_c, SCHED == 1 ? a2 : a0, SCHED == 2 ? b2 : b0);
+            if constexpr (LOAD && (S == 1 || SCHED != 0)) load_cluster(q_c, s_c, NAB == 3 ? a2 : a0, NBB == 3 ? b2 : b0);
             AXONN_FENCE();
             if constexpr (Q < NC - 1)
                 mfma_range(s_c, Int<P0 + Q * R / (NC - 1)>{}, Int<P0 + (Q + 1) * R / (NC - 1)>{});
@@ -322,22 +329,22 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
                 mfma_range(s_c, Int<P0 + R>{}, Int<NM>{});
             AXONN_FENCE();
         });
-        if constexpr (LOAD) {
-            if constexpr (SCHED == 0 ? S == 1 : (S == 0) == (SCHED == 1)) opa.advance();
-            if constexpr (SCHED == 0 ? S == 1 : (S == 0) == (SCHED == 2)) opb.advance();
+        if constexpr (LOAD) {   // the window moves on behind an operand's last load of the iteration
+            if constexpr (SCHED == 1 ? S == 0 : S == 1) opa.advance();
+            if constexpr (SCHED == 2 ? S == 0 : S == 1) opb.advance();
         }
         if constexpr (S == 1) {
             // the buffers move up: the one the loads have just gone to (SCHED 0: the running one) comes last
             const uint32_t a = a0, b = b0;
             a0 = a1;
             b0 = b1;
-            if constexpr (SCHED == 1) {
+            if constexpr (NAB == 3) {
                 a1 = a2;
                 a2 = a;
             } else {
                 a1 = a;
             }
-            if constexpr (SCHED == 2) {
+            if constexpr (NBB == 3) {
                 b1 = b2;
                 b2 = b;
             } else {
@@ -375,7 +382,8 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
         } else {
             wait_fragments(Int<1>{});
             AXONN_FENCE();
-            uint8_t* const epi = smem + (SCHED == 1 ? a2 : a1) + wave * (16 * TN * 2);   // an A buffer of an earlier iteration
+            static_assert(NW * 16 * TN * 2 <= (int)ABUF, "staging area of the streamed epilogue");
+            uint8_t* const epi = smem + (NAB == 3 ? a2 : a1) + wave * (16 * TN * 2);   // the A buffer of the iteration before
             uint16_t* const pc = C + (m0 + wm * TM) * (int64_t)ldc + n0 + wn * TN;
             static_for<MI>([&](auto i_c) __attribute__((always_inline)) {
                 constexpr int I = decltype(i_c)::value;

@@ -58,8 +58,8 @@ __global__ __launch_bounds__(512) void gemm_tile_kernel_k64p(
     int pid = (int)blockIdx.x;
     TileWork work = map_workgroup<false, true>(pid, total, K, tiles_m, tiles_n, group_m, sk);
 
-    using OpA = typename std::conditional<A_KC, OperandK64KContig<0, NW>, OperandK64MNContig<0, NW, MI / 2>>::type;
-    using OpB = typename std::conditional<B_KC, OperandK64KContig<REGION_B, NW>, OperandK64MNContig<REGION_B, NW, NI / 2>>::type;
+    using OpA = typename std::conditional<A_KC, OperandK64KContig<BM, 0, NW>, OperandK64MNContig<BM, 0, NW, MI / 2>>::type;
+    using OpB = typename std::conditional<B_KC, OperandK64KContig<BN, REGION_B, NW>, OperandK64MNContig<BN, REGION_B, NW, NI / 2>>::type;
     static_assert(OpA::QL == QL && OpB::QL == QL, "loads per wave");
     const uint32_t lds0 = lds_address(smem);
     OpA opa;

@@ -18,6 +18,8 @@ tile_kernel_t ring_kernel_large(bool split, int layout);                        
 tile_kernel_t ring_kernel_small(int bm, int bn, int wn, bool split, int layout);  // 256x128, 128x256 (wn 2, 4), 128x128
 // 64-k stages (gemm_tile_kernel_k64): 256 x 256, 2 x 4 waves
 tile_kernel_t k64_kernel(bool split, int layout);
+// the same on 256 x 128 and 128 x 256 tiles, 2 x 2 waves, three LDS buffers per operand (NT only, no split-K)
+tile_kernel_t k64_kernel_half(int bm, int bn, int layout);
 // the same with one resident workgroup per compute unit walking a list of tiles (gemm_tile_kernel_k64p)
 tile_kernel_t k64p_kernel(int layout);
 

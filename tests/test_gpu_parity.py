@@ -59,8 +59,12 @@ def run_gpu_guard_rows(op, M, N, K, layout, A_bits, B_bits, variant=-1):
 
 
 def tile_variants(layout=None):
-    """All MFMA tile variants (every one has a kernel for every layout); the last variant is the guarded one."""
-    return [v for v in range(1, edge_variant())]
+    """All MFMA tile variants that have a kernel for `layout` (the half tiles with 64-k stages exist for NT
+    only); the last variant is the guarded one."""
+    vs = list(range(1, edge_variant()))
+    if layout is None:
+        return vs
+    return [v for v in vs if B.variant_supports(v, 256, 256, 64 * 840, layout)]   # 840 K-steps: any number of K ranges up to 8
 
 
 def edge_variant():
@@ -224,7 +228,7 @@ def test_every_tile_variant_against_oracle(oracle_mod, layout):
             # a correct kernel sits near the bf16 rounding floor (2^-9 rms), far inside the bound
             assert nw < 4e-3, (B.variant_name(v), nw)
             ran += 1
-        assert ran == {1: 7, 2: 3, 4: 3}.get(splits, 2), (splits, ran)
+        assert ran == {1: 9 if layout == "NT" else 7, 2: 3, 4: 3}.get(splits, 2), (splits, ran)
     assert B.axonn_linear_split_k_timeouts() == 0
 
 

@@ -31,7 +31,7 @@ def test_static_scratch_entry_point_matches_the_registered_workspace_path(oracle
     U.shared_workspace()
     # first call: 128 large tiles, two K ranges (the whole static area); second, right behind it on the
     # same stream and smaller: 64 small tiles, two K ranges; a third that needs no scratch at all
-    cases = [("bwd_data", 2048, 4096, 4096, "NT", False), ("fwd", 1024, 1024, 8192, "NN", True),
+    cases = [("bwd_data", 2048, 4096, 8192, "NT", False), ("fwd", 1024, 1024, 8192, "NN", True),
              ("bwd_weight", 512, 768, 448, "TN", False)]
     names = [B.plan_name(M, N, K, lay, now=True) for _, M, N, K, lay, _ in cases]
     assert names[0].endswith("_sk2") and "_sk" in names[1] and "_sk" not in names[2], names
