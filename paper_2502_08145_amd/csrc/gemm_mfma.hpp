@@ -346,8 +346,9 @@ struct SplitK {
     uint32_t* timeouts;   // incremented when a reader gives up waiting (never, unless a writer died)
     uint32_t epoch;       // non-zero, differs from launch to launch: a flag left behind by a launch that died is never valid
     int splits;           // 1: no split
+    int skew;             // 64-k kernels: every writer's K range is this much shorter than K / splits, the reader's longer by the sum
 };
-constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~3 us per probe
+constexpr uint32_t kSplitSpinLimit = 1u << 19;   // x ~1 us per probe
 constexpr int kSplitRangePerXcdK = 32768;        // four K ranges: from this K on, one range per pair of XCDs
 
 // Workgroup -> output tile and K range.  The hardware hands workgroup b to XCD b % 8, in order of b

@@ -87,10 +87,18 @@ __device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const S
     if (krange != 0) {
         const size_t slot = (size_t)(krange - 1) * tiles + tile_id;
         f32x4* dst = reinterpret_cast<f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+        // device-scope stores: they go through the L2 to memory as they are issued, instead of sitting in
+        // the L2 until the release below writes the whole cache back (release 3.8 -> 0.8 us, the reader's
+        // wait for the flag 9.3 -> 6.5 us).  The s_nop is the wait state this chip wants between a store
+        // of more than 8 bytes and a VALU write to its data registers: the compiler inserts it behind its
+        // own stores, but cannot see this one (where the accumulators live in AGPRs the next instruction
+        // is the copy of the next block into the same registers).
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) dst[(i * NI + j) * 64] = acc[i][j];
+            for (int j = 0; j < NI; ++j)
+                asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(dst + (i * NI + j) * 64), "v"(acc[i][j]) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // acknowledged: the compiler does not count stores issued from asm
         // Cache maintenance is dear on a chip of eight private L2s (a device-scope release writes the
         // L2 back, an acquire invalidates it), so each workgroup does it once: the barrier orders
         // every thread's stores before thread 0's release, and thread 0's acquire before every
@@ -111,26 +119,35 @@ __device__ __forceinline__ bool split_k_exchange16(f32x4 (&acc)[MI][NI], const S
                     atomicAdd(sk.timeouts, 1u);
                     break;
                 }
-                __builtin_amdgcn_s_sleep(32);
+                __builtin_amdgcn_s_sleep(4);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // no stale cached copy of the slot
+            // The slot is as good as consumed (its writer does not touch the flag again): take the flag down.
+            // A launch replayed from a captured HIP graph carries the epoch of its capture, and must not
+            // find that value left over from the replay before.
+            __hip_atomic_store(&sk.flags[slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         const f32x4* src = reinterpret_cast<const f32x4*>(sk.partials) + slot * (BM * BN / 4) + in_slot;
+        // The slot comes from memory (the writer's L2 has written it back), a trip of a microsecond or
+        // two, so as many loads as there are registers for are in flight together: RB rows of blocks at a
+        // time, 64 registers, which the fragments no longer need (one row at a time, eight trips for a
+        // large tile instead of two, made the exchange of two K ranges 8 us longer).
+        constexpr int RB = MI % 4 == 0 ? 4 : MI % 2 == 0 ? 2 : 1;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            f32x4 v[NI];   // a row of blocks at a time: all its loads are in flight together
+        for (int i0 = 0; i0 < MI; i0 += RB) {
+            f32x4 v[RB][NI];
 #pragma unroll
-            for (int j = 0; j < NI; ++j) v[j] = __builtin_nontemporal_load(src + (i * NI + j) * 64);
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) v[i][j] = __builtin_nontemporal_load(src + ((i0 + i) * NI + j) * 64);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) acc[i][j] += v[j];
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) acc[i0 + i][j] += v[i][j];
             __builtin_amdgcn_sched_barrier(0);
         }
-        // The slot is consumed: take its flag down again.  A launch replayed from a captured HIP graph
-        // carries the epoch of its capture, and must not find that value left over from the replay before.
-        __syncthreads();
-        if (t == 0) __hip_atomic_store(&sk.flags[slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return false;
 }

@@ -187,9 +187,20 @@ __global__ __launch_bounds__(128 * WN) void gemm_tile_kernel_k64(
 
     // ---- workgroup -> output tile and K range ------------------------------------------------
     const TileWork work = map_workgroup<SPLITK, BM * BN == 256 * 256>(blockIdx.x, gridDim.x, K, tiles_m, tiles_n, group_m, sk);
-    const int tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange, ktotal = work.ktotal;
+    const int tile_m = work.tile_m, tile_n = work.tile_n, krange = work.krange;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int64_t k0 = (int64_t)krange * ktotal;
+    int ktotal = work.ktotal;
+    int64_t k0 = (int64_t)krange * ktotal;
+    if constexpr (SPLITK) {
+        // the writers' ranges are a little shorter than the reader's: their partial tiles are on their
+        // way while the reader still multiplies
+        if (krange == 0) {
+            ktotal += (sk.splits - 1) * sk.skew;
+        } else {
+            ktotal -= sk.skew;
+            k0 = (int64_t)work.ktotal + (int64_t)(sk.splits - 1) * sk.skew + (int64_t)(krange - 1) * ktotal;
+        }
+    }
 
     // ---- operands ------------------------------------------------------------------------------------
     using OpA = typename std::conditional<A_KC, OperandK64KContig<BM, 0, NW>, OperandK64MNContig<BM, 0, NW, MI / 2>>::type;
