@@ -28,11 +28,11 @@ def short(name: str) -> str:
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
         waves = "_w8" if int(wm) * int(wn) == 8 else ""
         return f"mfma{k16 or ''}_{bm}x{bn}{waves}{'_sk' if split == 'true' else ''}/{lay}"
-    m = re.search(r"gemm_tile_kernel_k64<(\d+), (true|false), (true|false), (true|false)>", name)
+    m = re.search(r"gemm_tile_kernel_k64<(\d+), (\d+), (\d+), (true|false), (true|false), (true|false), \d+>", name)
     if m:
-        wn, akc, bkc, split = m.groups()
+        bm, bn, wn, akc, bkc, split = m.groups()
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get((akc, bkc), "??")
-        return f"mfma16k64_256x256{'_w8' if wn == '4' else ''}{'_sk' if split == 'true' else ''}/{lay}"
+        return f"mfma16k64_{bm}x{bn}{'_w8' if wn == '4' else ''}{'_sk' if split == 'true' else ''}/{lay}"
     m = re.search(r"gemm_tile_kernel_k64p<(true|false), (true|false)>", name)
     if m:
         lay = {("true", "false"): "NN", ("true", "true"): "NT", ("false", "false"): "TN"}.get(m.groups(), "??")
