@@ -153,8 +153,9 @@ def variant_eff(args):
         del a, b, c
     print("variant                    eff NN   NT   TN   (TFLOP/s / 1200, mean over the shapes)")
     for name, d in rows.items():
-        e = [sum(d[l]) / len(d[l]) / 1200.0 for l in ("NN", "NT", "TN")]
-        print(f"{name:<26s} {e[0]:6.2f} {e[1]:4.2f} {e[2]:4.2f}")
+        # a variant may exist for one mode only
+        e = [f"{sum(d[l]) / len(d[l]) / 1200.0:4.2f}" if l in d else "   -" for l in ("NN", "NT", "TN")]
+        print(f"{name:<26s}   {e[0]} {e[1]} {e[2]}")
 
 
 def parse_smi(text):
