@@ -337,7 +337,11 @@ def main():
                 if w is not None and clk:
                     watts.append(w)
                     mhz += clk
-            if mhz:
+            if mhz and value > PEAK_BF16_TFLOPS * (sum(mhz) / len(mhz)) / 2400.0:
+                # a reading at which the step would exceed the peak at that clock was not taken under the step
+                # (seen with steps of several milliseconds: the clocks are read while they move)
+                log(f"board power/clock reading discarded: {sum(mhz) / len(mhz):.0f} MHz cannot have been the clock under this step")
+            elif mhz:
                 sclk = sum(mhz) / len(mhz)
                 board = {"socket_w": round(sum(watts) / len(watts)), "sclk_mhz": round(sclk),
                          "peak_at_sclk": round(PEAK_BF16_TFLOPS * sclk / 2400.0, 1),
