@@ -35,15 +35,21 @@ def hipcc() -> str:
 
 
 def source_id() -> str:
-    """Short hash of the kernel sources (csrc/ and the C header): names the build a measurement was
-    taken with, so that a stored counter reading can be told from one of an older kernel."""
+    """Short hash of the kernel sources (csrc/ and the C header) with comments and blank space taken out:
+    names the code a measurement was taken with, so that a stored counter reading can be told from one
+    of an older kernel, while a reworded comment does not orphan it."""
     import hashlib
+    import re
     h = hashlib.sha256()
     files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp", ".h")))
     files.append(os.path.join(os.path.dirname(HERE), "include", "axonn_linear.h"))
     for f in files:
+        text = open(f, "r", encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)          # block comments
+        text = re.sub(r"//[^\n]*", "", text)                        # line comments (no string in these sources holds //)
+        text = "\n".join(" ".join(l.split()) for l in text.splitlines() if l.strip())
         h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+        h.update(text.encode())
     return h.hexdigest()[:16]
 
 

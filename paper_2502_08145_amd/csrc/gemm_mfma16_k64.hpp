@@ -1,4 +1,5 @@
-// The tile kernel with LDS stages of 64 k and one barrier per 64 k, four or eight waves.
+// The tile kernel with LDS stages of 64 k and one barrier per 64 k, four or eight waves, tiles of 256 x 256,
+// 256 x 128 and 128 x 256.
 //
 // Why a kernel of its own.  In gemm_tile_kernel16 a K-contiguous operand is staged 32 k at a time:
 // a row of a stage is 64 bytes, half a cache line, so every direct load asks the L1 for sixteen
@@ -9,8 +10,8 @@
 //    then touches every bank once), a direct load fetches 8 rows x 128 B: eight full-line requests
 //    instead of sixteen half-line ones.  An MN-contiguous panel is two 32-k stages of
 //    OperandMNContig side by side;
-//  * two buffers of (256 + 256) x 64 k = 64 KB each; 2 x 2 waves (wave tile 128 x 128: every LDS
-//    byte is read twice, not three times) or 2 x 4 waves (128 x 64, two waves per SIMD);
+//  * per operand two buffers of BM (BN) x 64 k (256 x 256: 2 x 64 KB in all); 2 x 2 waves (every LDS
+//    byte is read twice, not three times) or 2 x 4 waves (256 x 256: wave tile 128 x 64, two waves per SIMD);
 //  * ONE barrier per 64 k.  An iteration is two sub-steps of 32 k.  During sub-step 0 of iteration i
 //    the fragments of its sub-step 1 are read; during sub-step 1, after the barrier, the fragments
 //    of iteration i+1 (other buffer), and the direct loads of iteration i+2 go out into the buffer
@@ -28,8 +29,8 @@
 // Measured: with eight waves it is the fastest kernel in all three modes (NN and NT: 3-4 % over the
 // 32-k kernel in the benchmark step, more for the split-K forms; TN: 2-4 % since C is streamed out as
 // non-temporal stores, with the reads and loads of a sub-step cut into six clusters instead of four);
-// the 32-k ring keeps NT at K above 24576 and TN with four and more K ranges.  With four waves it wins
-// only for NT without split-K, by a hair.  Fragments, MFMA order (mfma(Bfrag, Afrag)), accumulator
+// the 32-k ring keeps TN with four and more K ranges.  On the 256 x 256 tile four waves win only for NT
+// without split-K, by a hair (not instantiated); the half tiles run with four.  Fragments, MFMA order (mfma(Bfrag, Afrag)), accumulator
 // layout, split-K exchange, epilogue and the XCD-aware tile order are those of gemm_tile_kernel16.
 // (TN without split-K takes the epilogue into its last sub-step, see OVERLAP_EPI below.)
 #pragma once
