@@ -297,3 +297,24 @@ def test_amd_smi_text_is_parsed():
 """
     assert parse_smi(text) == (1398, [1915, 1865])
     assert parse_smi("no such fields") == (None, [])
+
+
+def test_source_hash_ignores_comments_and_blank_space(tmp_path, monkeypatch):
+    """The hash that ties stored counter readings to a build changes with the code, not with its comments."""
+    from paper_2502_08145_amd import build
+    csrc = tmp_path / "pkg" / "csrc"
+    inc = tmp_path / "include"
+    csrc.mkdir(parents=True)
+    inc.mkdir()
+    (inc / "axonn_linear.h").write_text("int f(void);\n")
+    monkeypatch.setattr(build, "CSRC", str(csrc))
+    monkeypatch.setattr(build, "HERE", str(tmp_path / "pkg"))
+    (csrc / "k.hpp").write_text("// a comment\nint   x = 1;   /* block\n comment */\n\nint y = 2;\n")
+    first = build.source_id()
+    (csrc / "k.hpp").write_text("int x = 1;\nint y = 2;  // another comment\n")
+    assert build.source_id() == first
+    (csrc / "k.hpp").write_text("int x = 1;\nint y = 3;\n")
+    assert build.source_id() != first
+    (csrc / "notes.orig").write_text("not a source file")
+    (csrc / "k.hpp").write_text("int x = 1;\nint y = 2;\n")
+    assert build.source_id() == first
