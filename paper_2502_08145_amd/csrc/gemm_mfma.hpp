@@ -389,7 +389,10 @@ __device__ __forceinline__ TileWork map_workgroup(int pid, int nwg, int K, int t
         }
         w.ktotal = K / splits;
     } else {
-        if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+        // XCD x runs the workgroups x, x + 8, ...: nwg / 8 of them, one more on the first nwg % 8 XCDs; it
+        // gets that many consecutive tiles of the sequence
+        const int x = pid & 7, rem = nwg & 7;
+        pid = x * (nwg >> 3) + (x < rem ? x : rem) + (pid >> 3);
     }
     w.tile_id = pid;
     const int group_sz = group_m * tiles_n;
