@@ -384,8 +384,12 @@ __device__ __forceinline__ TileWork map_workgroup(int pid, int nwg, int K, int t
             w.krange = splits - 1 - li / tp;
             pid = (pid & 7) * tp + li % tp;
         } else {
+            // any other count: range by range (writers first), and within a range the order of the
+            // non-split case: the workgroups of the range that one XCD runs take consecutive tiles
+            // (a tile's reader and writers then sit on different XCDs, which the exchange does not mind)
             w.krange = splits - 1 - pid / tiles;
-            pid = pid % tiles;
+            const int p = pid % tiles, j = p & 7, rem = tiles & 7;
+            pid = j * (tiles >> 3) + (j < rem ? j : rem) + (p >> 3);
         }
         w.ktotal = K / splits;
     } else {
