@@ -113,14 +113,28 @@ static std::vector<Variant> make_variants() {
         v.push_back(x);
     }
     // half tiles with 64-k stages: NT only (eff from 2048 x 4096 x 4096 and 4096^3 against the ring's half tiles)
-    auto k64h = [&](const char* name, int bm, int bn, double nt) {
-        Variant x{name, bm, bn, 256, k64_lds_bytes(bm, bn, 3), TileCfgK64::MIN_K, TileCfgK64::KS, 1, true,
+    auto k64h = [&](const char* name, int bm, int bn, int splits, double nt) {
+        Variant x{name, bm, bn, 256, k64_lds_bytes(bm, bn, 3), TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
                   {0.0, nt, 0.0}, {nullptr, nullptr, nullptr}};
-        for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel_half(bm, bn, l);
+        for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel_half(bm, bn, splits > 1, l);
         v.push_back(x);
     };
-    k64h("mfma16k64_256x128", 256, 128, 0.95);
-    k64h("mfma16k64_128x256", 128, 256, 0.94);
+    k64h("mfma16k64_256x128", 256, 128, 1, 0.95);
+    k64h("mfma16k64_128x256", 128, 256, 1, 0.94);
+    // split-K on the half tiles, for outputs that are narrow in one direction (2048 x 1152, 640 x 15360 ...) over a
+    // long K: the 64-k kernel for NT, the 32-k ring for NN and TN
+    // (two and three ranges only: with four and more the reader's turn at the slots costs more than the large
+    // tile's split-K or 128 x 128 tiles do on the same outputs)
+    static const char* const h1_sk[] = {"mfma16k64_256x128_sk2", "mfma16k64_256x128_sk3"};
+    static const char* const h2_sk[] = {"mfma16k64_128x256_sk2", "mfma16k64_128x256_sk3"};
+    static const char* const r1_sk[] = {"mfma16_256x128_sk2", "mfma16_256x128_sk3"};
+    static const char* const r2_sk[] = {"mfma16_128x256_sk2", "mfma16_128x256_sk3"};
+    for (int sp = 2; sp <= 3; ++sp) {
+        k64h(h1_sk[sp - 2], 256, 128, sp, 0.85);
+        k64h(h2_sk[sp - 2], 128, 256, sp, 0.84);
+        ring(r1_sk[sp - 2], 256, 128, 2, sp, TileCfg16<256, 128, 2, 2>::LDS_BYTES, TileCfg16<256, 128, 2, 2>::MIN_K, 0.80, 0.70, 0.84);
+        ring(r2_sk[sp - 2], 128, 256, 2, sp, TileCfg16<128, 256, 2, 2>::LDS_BYTES, TileCfg16<128, 256, 2, 2>::MIN_K, 0.80, 0.68, 0.82);
+    }
     static const char* const k64_sk[] = {"mfma16k64_256x256_w8_sk2", "mfma16k64_256x256_w8_sk3", "mfma16k64_256x256_w8_sk4", "mfma16k64_256x256_w8_sk5",
                                          "mfma16k64_256x256_w8_sk6", "mfma16k64_256x256_w8_sk7", "mfma16k64_256x256_w8_sk8"};
     for (int sp = 2; sp <= 8; ++sp) k64(k64_sk[sp - 2], sp);
@@ -273,7 +287,9 @@ static double model_time(int v, int64_t M, int64_t N, int64_t K, int layout, boo
     // large tiles: the partial tiles travel through HBM, (splits - 1) x 256 KB per tile written and
     // read back at 4-5 TB/s (0.1 us, or 4 units of k, per slot), and the reader of a tile takes its
     // slots one after the other at one CU's rate (2.5 us, 100 units, per slot)
-    const double fixed_large = 4.0 * tiles * (var.splits - 1) + 100.0 * (var.splits - 1);
+    // (half tiles: half the bytes per slot in flight; what the reader pays per slot is mostly latency)
+    const bool half_tile = var.bm * var.bn < 256 * 256;
+    const double fixed_large = 4.0 * tiles * (var.splits - 1) * (var.bm * var.bn) / 65536.0 + (half_tile ? 160.0 : 100.0) * (var.splits - 1);
     const double k_cost = (double)(K / var.splits) + kFixedK +
                           (var.splits == 1 ? 0.0 : var.bm * var.bn <= 128 * 128 ? fixed_small : fixed_large);
     double e = var.eff[layout];

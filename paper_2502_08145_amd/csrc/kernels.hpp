@@ -15,11 +15,11 @@ typedef void (*tile_kernel_t)(const uint16_t*, const uint16_t*, uint16_t*, int, 
 // layout: 0 NN, 1 NT, 2 TN.  nullptr: no such kernel.
 // 32-k LDS ring (gemm_tile_kernel16): tile bm x bn, 2 x wn waves, with or without split-K
 tile_kernel_t ring_kernel_large(bool split, int layout);                          // 256 x 256, 2 x 4 waves
-tile_kernel_t ring_kernel_small(int bm, int bn, int wn, bool split, int layout);  // 256x128, 128x256 (wn 2, 4), 128x128
+tile_kernel_t ring_kernel_small(int bm, int bn, int wn, bool split, int layout);  // 256x128, 128x256 (wn 2; wn 4 without split-K), 128x128
 // 64-k stages (gemm_tile_kernel_k64): 256 x 256, 2 x 4 waves
 tile_kernel_t k64_kernel(bool split, int layout);
-// the same on 256 x 128 and 128 x 256 tiles, 2 x 2 waves, three LDS buffers per operand (NT only, no split-K)
-tile_kernel_t k64_kernel_half(int bm, int bn, int layout);
+// the same on 256 x 128 and 128 x 256 tiles, 2 x 2 waves, three LDS buffers per operand (NT only)
+tile_kernel_t k64_kernel_half(int bm, int bn, bool split, int layout);
 // the same with one resident workgroup per compute unit walking a list of tiles (gemm_tile_kernel_k64p)
 tile_kernel_t k64p_kernel(int layout);
 

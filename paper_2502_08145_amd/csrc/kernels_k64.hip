@@ -26,10 +26,12 @@ tile_kernel_t k64_kernel(bool split, int layout) {
 // tiles (2048 x 4096 x 4096: 1018 against 794 TFLOP/s; 4096^3: 1141 against 949); with an MN-contiguous
 // operand it is 15-30 % BEHIND the ring (NN 743 against 990, TN 704 against 904), like every schedule
 // tried that issues such an operand's loads anywhere but straight after the barrier.
-tile_kernel_t k64_kernel_half(int bm, int bn, int layout) {
+tile_kernel_t k64_kernel_half(int bm, int bn, bool split, int layout) {
     if (layout != 1) return nullptr;
-    if (bm == 256 && bn == 128) return gemm_tile_kernel_k64<256, 128, 2, true, true, false, 3>;
-    if (bm == 128 && bn == 256) return gemm_tile_kernel_k64<128, 256, 2, true, true, false, 3>;
+    if (bm == 256 && bn == 128)
+        return split ? gemm_tile_kernel_k64<256, 128, 2, true, true, true, 3> : gemm_tile_kernel_k64<256, 128, 2, true, true, false, 3>;
+    if (bm == 128 && bn == 256)
+        return split ? gemm_tile_kernel_k64<128, 256, 2, true, true, true, 3> : gemm_tile_kernel_k64<128, 256, 2, true, true, false, 3>;
     return nullptr;
 }
 
