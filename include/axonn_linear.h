@@ -275,9 +275,9 @@ int axonn_linear_split_k_timeouts(uint64_t *count);
  * guarded MFMA kernel for any M, N, K >= 1; the others are MFMA tile kernels ("_w8": 8 waves,
  * "_sk2" ... "_sk8": split-K over that many workgroups).  Host-only queries: no GPU is touched. */
 int axonn_linear_num_variants(void);
-/* Name such as "mfma_256x256"; NULL if `variant` is out of range. */
+/* Name such as "mfma16k64_256x256_w8_sk2"; NULL if `variant` is out of range. */
 const char *axonn_linear_variant_name(int variant);
-/* 1 if `variant` can run (M,N,K,layout), else 0. */
+/* 1 if `variant` can run (M,N,K,layout), else 0 (some variants exist for one layout only). */
 int axonn_linear_variant_supports(int variant, int64_t M, int64_t N, int64_t K, int layout);
 /* The variant the library would pick for ONE launch over the whole output (pure host logic,
  * ignores any override); negative error code on bad arguments. */
