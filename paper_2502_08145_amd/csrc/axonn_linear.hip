@@ -87,7 +87,7 @@ static std::vector<Variant> make_variants() {
         v.push_back(x);
     };
     auto k64 = [&](const char* name, int splits) {
-        Variant x{name, 256, 256, 512, TileCfgK64::LDS3_BYTES, TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
+        Variant x{name, 256, 256, 512, k64_lds_bytes(256, 256, 1), TileCfgK64::MIN_K, TileCfgK64::KS, splits, true,
                   {1.17, 1.17, 1.15}, {nullptr, nullptr, nullptr}};
         for (int l = 0; l < 3; ++l) x.fn[l] = k64_kernel(splits > 1, l);
         v.push_back(x);

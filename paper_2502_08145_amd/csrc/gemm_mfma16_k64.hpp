@@ -43,8 +43,6 @@ struct TileCfgK64 {
     static constexpr int KS = 64;                                  // k per LDS buffer
     static constexpr int A_BYTES = BM * KS * 2, BUF_BYTES = (BM + BN) * KS * 2;
     static constexpr int LDS_BYTES = 2 * BUF_BYTES;                // 128 KB; the epilogue needs BM*BN*2 = 128 KB
-    static constexpr int B_BYTES = BN * KS * 2;
-    static constexpr int LDS3_BYTES = LDS_BYTES + A_BYTES;         // 160 KB: with a third buffer for one operand
     static constexpr int MIN_K = 2 * KS;                           // the prologue fills both buffers
 };
 
