@@ -665,6 +665,40 @@ def test_model_zoo_shard_shapes_sampled(oracle_mod, h, layer, d_in, d_out):
         U.assert_close(got[ii, jj], ref, f"{g['name']} {g['layout']} {B.plan_name(M, N, K, g['layout'])}")
 
 
+def _random_shapes():
+    """Seeded shapes off the beaten track: tile counts that are odd, not multiples of 8, or one and a
+    fraction rounds; outputs narrow in one direction over a long K; M and N multiples of 128, K of 64."""
+    rng = np.random.default_rng(81450)
+    cases = []
+    for layout in LAYOUTS:
+        for _ in range(7):
+            narrow = rng.random() < 0.4
+            M = int(rng.integers(1, 40)) * 128
+            N = int(rng.integers(1, 12 if narrow else 40)) * 128
+            if rng.random() < 0.5:
+                M, N = N, M
+            K = int(rng.integers(2, 300 if narrow else 96)) * 64
+            cases.append((layout, M, N, K))
+    return cases
+
+
+@pytest.mark.parametrize("layout,M,N,K", _random_shapes())
+def test_random_shapes_integer_data_sampled_bit_for_bit(oracle_mod, layout, M, N, K):
+    """Automatic plan on seeded random shapes, small-integer data (every partial sum exact in fp32, so the
+    result does not depend on how K is cut up or in which order partial tiles are added): sampled rows,
+    columns and one element per 128 x 128 block must equal the oracle's bf16 rounding bit for bit."""
+    a = synth.integer_bf16(7000 + M + K, (M, K), -3, 3)
+    b = synth.integer_bf16(7001 + N + K, (K, N), -3, 3)
+    A, Bm = store(a, b, layout)
+    ii, jj = _sample_positions(M, N, seed=M * 7 + N * 3 + K)
+    want = U.f64_to_bf16_bits_rne(oracle_mod.gemm_at(M, N, K, layout, A, Bm, ii, jj))
+    got = run_gpu("fwd", M, N, K, layout, A, Bm)
+    bad = np.flatnonzero(got[ii, jj] != want)
+    assert bad.size == 0, (f"{layout} {M}x{N}x{K} plan {B.plan_name(M, N, K, layout)}: {bad.size} sampled outputs differ, "
+                           f"first at ({ii[bad[0]]}, {jj[bad[0]]})")
+    assert B.axonn_linear_split_k_timeouts() == 0
+
+
 def test_model_zoo_plans_with_odd_split_counts_and_two_launches(oracle_mod):
     """Among the model-zoo shard shapes the planner picks split-K with 3, 5 and 6 K ranges (7 is never
     chosen there; test_every_tile_variant_against_oracle covers it) and plans of two launches: one
