@@ -318,3 +318,24 @@ def test_source_hash_ignores_comments_and_blank_space(tmp_path, monkeypatch):
     (csrc / "notes.orig").write_text("not a source file")
     (csrc / "k.hpp").write_text("int x = 1;\nint y = 2;\n")
     assert build.source_id() == first
+
+
+def test_planner_choices_that_the_design_notes_describe():
+    """Host-only: the selection model on a few shapes whose plans are stated in the design notes."""
+    name = lambda M, N, K, lay: B.plan_name(M, N, K, lay)
+    # narrow outputs over a long K: half tiles in three K ranges (64-k kernel for NT, 32-k ring for NN)
+    assert name(2048, 1152, 36864, "NT") == "mfma16k64_256x128_sk3"
+    assert name(2048, 1152, 36864, "NN") == "mfma16_256x128_sk3"
+    # 128 large tiles at K = 4096: half tiles with 64-k stages for NT, the ring's half tiles for NN
+    assert name(2048, 4096, 4096, "NT") == "mfma16k64_256x128"
+    assert name(2048, 4096, 4096, "NN") == "mfma16_128x256"
+    # the resident kernel: TN from three rounds on up to K = 8192, NN at K <= 2048; not at long K
+    assert name(4096, 16384, 2048, "TN") == "mfma16k64p_256x256_w8"
+    assert name(4096, 16384, 2048, "NN") == "mfma16k64p_256x256_w8"
+    assert name(16384, 16384, 16384, "TN") == "mfma16k64_256x256_w8"
+    assert name(4096, 16384, 2048, "NT") == "mfma16k64_256x256_w8"
+    # NT at long K stays on the 64-k kernel (its A panel is triple-buffered), also when split
+    assert name(8192, 8192, 32768, "NT") == "mfma16k64_256x256_w8"
+    assert name(2048, 2048, 65536, "NT").startswith("mfma16k64_256x256_w8_sk")
+    # one and a half rounds of large tiles: two launches
+    assert "+" in name(2048, 12288, 4096, "NN")
